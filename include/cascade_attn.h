@@ -1,0 +1,165 @@
+/*
+ * cascade_attn.h -- C ABI of the block-cascaded self-attention library for MI355X (gfx950).
+ *
+ * One forward of a block-cascaded video DiT layer: the queries of several in-flight
+ * latent-frame blocks, each at its own denoising step, attend to a shared KV pool that
+ * holds the clean cache of finished blocks (rolling window, optional sink) and the K/V
+ * of the in-flight blocks themselves (paper Sec. 3.2 "mini-batches ... with shared
+ * attention", Sec. 3.3 "shared KV pool", Alg. 1).
+ *
+ * Conventions
+ *   - Every function returns int32_t: CA_OK (0) or a negative CA_E* code.  Nothing throws,
+ *     aborts or prints.  On error no metadata changes and no GPU work is enqueued.
+ *   - "dev" pointers are device (HBM) addresses, everything else is host memory.
+ *   - The caller owns every device buffer (the pool included) and the HIP stream.  ca_ctx
+ *     owns host metadata only.  Device calls are asynchronous on the given stream (a
+ *     hipStream_t passed as void*, NULL = the default stream) and never synchronise; device
+ *     buffers must stay valid until that work has run.
+ *   - A context is not thread-safe; calls on one context that overlap on the GPU in
+ *     different streams are the caller's to order.
+ *   - Tensors are [token, head, dim] with element strides tok_stride / head_stride and unit
+ *     stride along dim.  dtype is that of ca_config.dtype (bf16 bit patterns or fp32).
+ *   - Token n of a block is at (frame, row, col) = (Fb*g + n / (gh*gw), (n / gw) % gh, n % gw)
+ *     for block index g: a block is `frames_per_block` consecutive latent frames (Sec. 3.2).
+ *
+ * Rotary embedding (not described in the paper; convention of the Wan-family DiT it adapts):
+ * head_dim is cut into three runs of consecutive (even, odd) pairs of rope_dim_t, rope_dim_h,
+ * rope_dim_w dims for the frame / row / col axes; pair j of an axis with Da dims is rotated
+ * by angle pos_a * theta^(-2j/Da): (u, v) -> (u cos - v sin, u sin + v cos).  Positions are
+ * absolute and K is stored rotated, so nothing is re-rotated when the window slides.
+ *
+ * Pool layout.  Slots 0 .. sink+window+max_inflight-1, each holding one block of
+ * P = ceil(L / page_tokens) pages per head.  Block g < sink_blocks lives in slot g; any
+ * other block in slot sink + ((g - sink) mod (window + max_inflight)).  Page `p` of slot `s`,
+ * head `h` is page pair number (s*P + p)*heads + h; a page pair is a K page followed by a
+ * V page, each page_tokens*head_dim elements.  Inside a page:
+ *   fp32 : K and V row-major [token][dim].
+ *   bf16 (head_dim 128, page_tokens 128): 256-byte rows of sixteen 16-byte chunks, chunk c of
+ *          row r stored at chunk position c ^ (r & 15) (LDS-bank swizzle kept in HBM so a page
+ *          is copied to LDS linearly).  K page: row = token, chunk c = dims 8c..8c+7.
+ *          V page: row = dim, chunk c = eight tokens: element e of chunk c is token
+ *          16*(c/2) + perm[8*(c%2) + e], perm = {0,1,2,3,8,9,10,11,4,5,6,7,12,13,14,15}
+ *          (the order in which an MFMA 32x32 accumulator hands P to the next MFMA).
+ *   Rows/tokens past the end of a block's last page are stored as zeros.
+ */
+#ifndef CASCADE_ATTN_H
+#define CASCADE_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CA_OK = 0,
+  CA_EINVAL = -1,       /* null pointer, bad size/stride, inconsistent config               */
+  CA_ENOSPC = -2,       /* the block's slot is still held by another block                  */
+  CA_ENOENT = -3,       /* block not resident                                                */
+  CA_ESTATE = -4,       /* wrong state: evict a sink, promote a clean block, rewrite a clean */
+  CA_EUNSUPPORTED = -5, /* dtype / head_dim / page size the kernels do not cover             */
+  CA_ENOPOOL = -6,      /* device work asked of a metadata-only context                      */
+  CA_EDEVICE = -7       /* the HIP runtime refused a launch                                  */
+};
+
+enum { CA_F32 = 0, CA_BF16 = 1 };
+enum { CA_BIDIRECTIONAL = 0, CA_BLOCK_CAUSAL = 1 };          /* Sec. 3.4 / Sec. 4.2 "causal P4" */
+enum { CA_FREE = 0, CA_NOISY = 1, CA_CLEAN = 2, CA_SINK = 3 };
+
+typedef struct ca_ctx ca_ctx;
+
+typedef struct {
+  int32_t heads, head_dim;
+  int32_t frames_per_block, grid_h, grid_w;      /* L = frames_per_block*grid_h*grid_w       */
+  int32_t rope_dim_t, rope_dim_h, rope_dim_w;    /* even, sum == head_dim                    */
+  double  rope_theta;
+  int32_t sink_blocks, window_blocks, max_inflight;
+  int32_t page_tokens;
+  int32_t dtype;                                 /* CA_F32 | CA_BF16                         */
+} ca_config;
+
+typedef struct {
+  int32_t slot;
+  int32_t state;          /* CA_NOISY | CA_CLEAN | CA_SINK                                   */
+  int64_t block_id;
+  int32_t timestep;       /* denoising timestep the stored K/V were computed at              */
+  int32_t prompt_epoch;   /* prompt the block was last tagged with                           */
+} ca_slot_info;
+
+/* Bytes of device memory the pool needs for this configuration (0 if the config is invalid). */
+size_t ca_pool_bytes(const ca_config* cfg);
+
+/* Create a context over a caller-allocated pool of at least ca_pool_bytes() bytes, 256-byte
+ * aligned.  pool_dev == NULL with pool_bytes == 0 creates a metadata-only context: the cache
+ * calls keep the slot map and tags but enqueue nothing, and cascade_attn_forward /
+ * rope3d_apply return CA_ENOPOOL.  The pool's contents are never cleared by the library. */
+int32_t ca_create(const ca_config* cfg, void* pool_dev, size_t pool_bytes, ca_ctx** out);
+int32_t ca_destroy(ca_ctx* ctx);
+
+/* Publish one block's K/V to the shared pool (Sec. 3.3): rotate K by the block's positions,
+ * store K and V into the pages of the block's slot, tag the entry NOISY(timestep, epoch).
+ * A block that is already resident and NOISY is rewritten in place (its next denoising step).
+ * k_dev, v_dev: [L, heads, head_dim], K before rotation.  slot_out (optional) gets the slot. */
+int32_t kv_cache_append(ca_ctx* ctx, int64_t block_id, int32_t timestep, int32_t prompt_epoch,
+                        const void* k_dev, const void* v_dev,
+                        int64_t tok_stride, int64_t head_stride,
+                        void* hip_stream, int32_t* slot_out);
+
+/* The block has run its cache step tc (Alg. 1: "block b completed tc"): NOISY -> CLEAN, or
+ * -> SINK when block_id < sink_blocks (Sec. 3.3, first block kept as sink). */
+int32_t kv_cache_promote(ca_ctx* ctx, int64_t block_id);
+
+/* Drop a block from the rolling window (Sec. 2.3 / 3.3); a SINK entry refuses (CA_ESTATE). */
+int32_t kv_cache_evict(ca_ctx* ctx, int64_t block_id);
+
+/* Prompt switch without re-caching (Sec. 3.5): NOISY entries take the new prompt epoch;
+ * CLEAN/SINK entries, the slot map and all K/V bytes stay as they are. */
+int32_t kv_cache_retag(ca_ctx* ctx, int32_t new_prompt_epoch);
+
+/* Occupied slots in ascending slot order.  n_out gets the number of occupied slots even when
+ * it exceeds cap (then only cap entries are written). */
+int32_t kv_cache_snapshot(const ca_ctx* ctx, ca_slot_info* out, int32_t cap, int32_t* n_out);
+
+/* Physical page-pair number of (block, page, head), the rule stated above; CA_ENOENT if the
+ * block is not resident. */
+int32_t kv_cache_page_index(const ca_ctx* ctx, int64_t block_id, int32_t page, int32_t head,
+                            int64_t* index_out);
+
+/* Rotate n_tokens tokens that are consecutive in the video, starting at the first token of
+ * latent frame first_frame (frame-major, then row, then col).  x_dev == y_dev is allowed. */
+int32_t rope3d_apply(const ca_ctx* ctx, const void* x_dev, void* y_dev, int64_t n_tokens,
+                     int64_t first_frame, int64_t tok_stride, int64_t head_stride,
+                     void* hip_stream);
+
+/* Block-cascaded attention.  q_dev / out_dev: [n_inflight*L, heads, head_dim] contiguous,
+ * rotated queries of the in-flight blocks in the order of inflight_block_ids, which must be
+ * strictly ascending, resident and NOISY (their K/V appended for this step).
+ * KV sequence: SINK blocks, CLEAN blocks by ascending id, then the in-flight blocks.  Query
+ * block i sees every SINK/CLEAN block, and in-flight block j iff mode == CA_BIDIRECTIONAL or
+ * j <= i; inside a visible block pair every token pair is visible (Sec. 3.1).  Softmax scale
+ * is 1/sqrt(head_dim).  Pages of invisible blocks are never read. */
+int32_t cascade_attn_forward(ca_ctx* ctx, const void* q_dev,
+                             const int64_t* inflight_block_ids, int32_t n_inflight,
+                             int32_t mode, void* out_dev, void* hip_stream);
+
+/* The mask cascade_attn_forward would use: vis[i*n_kv + r] in {0,1} for query block i and
+ * KV block r of the KV sequence, kv_block_ids[r] its block id.  cap = capacity of
+ * kv_block_ids (and vis holds n_inflight*cap bytes); n_kv_out gets the sequence length. */
+int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids,
+                            int32_t n_inflight, int32_t mode, uint8_t* vis,
+                            int64_t* kv_block_ids, int32_t cap, int32_t* n_kv_out);
+
+/* Selects an attention kernel variant for experiments (0 = default).  Unknown values are
+ * rejected with CA_EINVAL. */
+int32_t ca_set_kernel_variant(ca_ctx* ctx, int32_t variant);
+
+const char* ca_strerror(int32_t code);
+
+/* Text of the HIP error behind the calling thread's most recent CA_EDEVICE ("" if none). */
+const char* ca_last_device_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CASCADE_ATTN_H */

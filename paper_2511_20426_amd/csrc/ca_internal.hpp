@@ -1,0 +1,105 @@
+// Internal declarations shared by the host metadata, the C-ABI layer and the kernel launchers.
+// Not part of the public boundary (that is include/cascade_attn.h).
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "cascade_attn.h"
+
+namespace ca {
+
+constexpr int kMaxPairs = 64;      // head_dim <= 128
+constexpr int kMaxKvBlocks = 32;   // sink + window + max_inflight
+constexpr int kMaxInflight = 8;
+
+// ----------------------------------------------------------------------------- host metadata
+// Slot map, tags and the visibility rule; plain C++, no HIP (Sec. 3.3: shared KV pool with a
+// rolling window and a sink block; Alg. 1: blocks move NOISY -> CLEAN when they complete tc).
+class CacheMeta {
+ public:
+  static int32_t validate(const ca_config& c);
+  explicit CacheMeta(const ca_config& c);
+
+  const ca_config& cfg() const { return cfg_; }
+  int block_tokens() const { return L_; }
+  int pages_per_block() const { return P_; }
+  int n_slots() const { return n_slots_; }
+  size_t elem_bytes() const { return cfg_.dtype == CA_BF16 ? 2 : 4; }
+  size_t page_elems() const { return size_t(cfg_.page_tokens) * cfg_.head_dim; }
+  size_t pair_bytes() const { return 2 * page_elems() * elem_bytes(); }
+  size_t pool_bytes() const { return size_t(n_slots_) * P_ * cfg_.heads * pair_bytes(); }
+
+  int32_t slot_of(int64_t g, int32_t* slot) const;       // the fixed rule, resident or not
+  int32_t find(int64_t g, int32_t* slot) const;          // CA_ENOENT unless resident
+  int32_t check_append(int64_t g, int32_t* slot) const;  // what append would do, no change
+  void commit_append(int32_t slot, int64_t g, int32_t timestep, int32_t epoch);
+  int32_t promote(int64_t g);
+  int32_t evict(int64_t g);
+  void retag(int32_t epoch);
+  int32_t snapshot(ca_slot_info* out, int32_t cap, int32_t* n_out) const;
+
+  // KV sequence of one forward and the block-pair mask.  kv_ids/kv_slots get n_kv entries,
+  // n_vis[i] = number of leading KV entries query block i sees (the sequence is ordered so
+  // that the visible set of every query block is a prefix).
+  int32_t plan_forward(const int64_t* inflight, int32_t n_inflight, int32_t mode,
+                       std::vector<int64_t>* kv_ids, std::vector<int32_t>* kv_slots,
+                       std::vector<int32_t>* n_vis) const;
+
+  const double* rope_freq() const { return freq_; }      // per pair, kMaxPairs entries
+
+ private:
+  ca_config cfg_;
+  int L_, P_, n_slots_;
+  std::vector<int64_t> block_;
+  std::vector<int32_t> state_, timestep_, epoch_;
+  double freq_[kMaxPairs];
+};
+
+// ----------------------------------------------------------------------------- kernel launchers
+struct RopeGeom {
+  double freq[kMaxPairs];   // angle per unit position for pair j
+  int32_t pairs_t, pairs_h; // pairs [0,pairs_t) use the frame, [pairs_t,pairs_t+pairs_h) the row, rest the col
+  int32_t grid_h, grid_w;
+  int32_t heads, head_dim;
+};
+
+// y = rope(x) on [n_tokens, heads, head_dim]; token n sits at frame first_frame + n/(gh*gw).
+int32_t launch_rope_apply(const RopeGeom& g, int dtype, const void* x, void* y, int64_t n_tokens,
+                          int64_t first_frame, int64_t tok_stride, int64_t head_stride,
+                          void* stream);
+
+// Fused K-rotation + K/V page store of one block into its slot.
+int32_t launch_cache_write(const RopeGeom& g, int dtype, const void* k, const void* v,
+                           int64_t tok_stride, int64_t head_stride, int64_t first_frame,
+                           int32_t block_tokens, int32_t page_tokens, int32_t pages_per_block,
+                           int32_t slot, void* pool, void* stream);
+
+struct AttnPlan {
+  int32_t heads, head_dim, page_tokens, pages_per_block, block_tokens;
+  int32_t n_q_blocks;                 // in-flight blocks; query rows are n_q_blocks * block_tokens
+  int32_t n_kv;                       // length of the KV sequence
+  int32_t kv_slot[kMaxKvBlocks];
+  int32_t n_vis[kMaxInflight];        // visible prefix length per query block
+  int32_t uniform;                    // every query block sees the whole sequence
+};
+
+int32_t launch_attn_f32(const AttnPlan& p, const void* q, void* out, const void* pool, void* stream);
+int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
+                         void* stream);
+int32_t attn_bf16_variant_ok(int variant);
+
+// Launchers end with this: CA_OK, or CA_EDEVICE after recording the HIP error text.
+int32_t finish_launch(const char* what);
+const char* last_device_error();
+
+}  // namespace ca
+
+struct ca_ctx {
+  ca::CacheMeta meta;
+  void* pool;
+  size_t pool_bytes;
+  int32_t variant;
+  explicit ca_ctx(const ca_config& c) : meta(c), pool(nullptr), pool_bytes(0), variant(0) {}
+};

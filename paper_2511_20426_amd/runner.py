@@ -1,0 +1,79 @@
+"""Torch plumbing around the C ABI: device memory for the pool and the current HIP stream.
+
+No arithmetic of the method happens here; every tensor handed to the library is passed as a
+raw device address.
+"""
+from __future__ import annotations
+
+from typing import Sequence
+
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(dtype: str):
+    return {"bf16": torch.bfloat16, "f32": torch.float32}[dtype]
+
+
+class CascadePool:
+    """A ca_ctx over a pool tensor allocated with torch on the current device."""
+
+    def __init__(self, *, heads, head_dim, frames_per_block, grid_h, grid_w, rope_dims, rope_theta,
+                 sink_blocks, window_blocks, max_inflight, page_tokens, dtype, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("CascadePool needs a GPU; use binding.Context(cfg) for metadata-only work")
+        self.dtype = dtype
+        self.device = torch.device(device)
+        self.cfg = B.make_config(heads=heads, head_dim=head_dim, frames_per_block=frames_per_block,
+                                 grid_h=grid_h, grid_w=grid_w, rope_dims=rope_dims, rope_theta=rope_theta,
+                                 sink_blocks=sink_blocks, window_blocks=window_blocks,
+                                 max_inflight=max_inflight, page_tokens=page_tokens, dtype=dtype)
+        nbytes = B.pool_bytes(self.cfg)
+        if nbytes == 0:
+            raise ValueError("configuration rejected by ca_pool_bytes")
+        self.pool = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.ctx = B.Context(self.cfg, self.pool.data_ptr(), nbytes)
+        self.block_tokens = frames_per_block * grid_h * grid_w
+        self.frames_per_block = frames_per_block
+        self.heads, self.head_dim = heads, head_dim
+
+    @classmethod
+    def for_workload(cls, w, device="cuda:0"):
+        return cls(heads=w.heads, head_dim=w.head_dim, frames_per_block=w.frames_per_block,
+                   grid_h=w.grid_h, grid_w=w.grid_w, rope_dims=w.rope_dims, rope_theta=w.rope_theta,
+                   sink_blocks=w.sink_blocks, window_blocks=max(w.window_blocks, w.n_cached),
+                   max_inflight=w.max_inflight, page_tokens=w.page_tokens, dtype=w.dtype, device=device)
+
+    def _stream(self) -> int:
+        return torch.cuda.current_stream(self.device).cuda_stream
+
+    def _check(self, t: torch.Tensor) -> None:
+        assert t.is_cuda and t.dtype == torch_dtype(self.dtype) and t.dim() == 3 and t.stride(2) == 1
+        assert t.shape[1] == self.heads and t.shape[2] == self.head_dim
+
+    def append(self, block_id: int, timestep: int, epoch: int, k: torch.Tensor, v: torch.Tensor) -> int:
+        self._check(k); self._check(v)
+        assert k.shape[0] == self.block_tokens and k.stride() == v.stride() and k.shape == v.shape
+        return self.ctx.kv_cache_append(block_id, timestep, epoch, k.data_ptr(), v.data_ptr(),
+                                        k.stride(0), k.stride(1), self._stream())
+
+    def rope(self, x: torch.Tensor, first_frame: int, out: torch.Tensor | None = None) -> torch.Tensor:
+        self._check(x)
+        if out is None:
+            assert x.is_contiguous(), "pass `out` with the strides of a non-contiguous input"
+            out = torch.empty_like(x)
+        y = out
+        assert y.stride() == x.stride() and y.shape == x.shape
+        self.ctx.rope3d_apply(x.data_ptr(), y.data_ptr(), x.shape[0], first_frame, x.stride(0),
+                              x.stride(1), self._stream())
+        return y
+
+    def forward(self, q_rot: torch.Tensor, inflight: Sequence[int], mode: int,
+                out: torch.Tensor | None = None) -> torch.Tensor:
+        self._check(q_rot)
+        assert q_rot.is_contiguous() and q_rot.shape[0] == len(inflight) * self.block_tokens
+        o = torch.empty_like(q_rot) if out is None else out
+        assert o.is_contiguous()
+        self.ctx.cascade_attn_forward(q_rot.data_ptr(), list(inflight), mode, o.data_ptr(), self._stream())
+        return o

@@ -1,0 +1,253 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle on the same seeded inputs.
+
+Bars: cache slots, page indices, visibility and V pages bit-exact; bf16 outputs within
+max-abs 2e-2 and relative L2 5e-3 of the oracle; fp32 outputs within 2e-5 / 1e-5.
+"""
+import time
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import cascade_oracle as orc
+from tests import _harness as Hn
+
+pytestmark = pytest.mark.gpu
+
+BI, CA = orc.BIDIRECTIONAL, orc.BLOCK_CAUSAL
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _one_shot(w, mode, scale=None, seed=None, rows=None, heads=None, first_block=0):
+    """Cached blocks first_block..first_block+n_cached-1, in-flight ones right after."""
+    q, k, v = W.draw_config(w, seed=seed, scale=scale)
+    cached = list(range(first_block, first_block + w.n_cached))
+    infl = list(range(first_block + w.n_cached, first_block + w.n_cached + w.n_inflight))
+    pool = Hn.gpu_setup(w, k, v, cached, infl)
+    out = Hn.gpu_forward(w, pool, q, infl, mode)
+    ref = Hn.oracle_forward(w, q, k, v, cached, infl, mode, rows=rows, heads=heads)
+    L = w.block_tokens
+    outs = W.split_blocks(out, L)
+    if heads is not None:
+        outs = [o[:, list(heads)] for o in outs]
+    if rows is not None:
+        outs = [o[np.asarray(r)] for o, r in zip(outs, rows)]
+    return outs, ref
+
+
+# --------------------------------------------------------------------------- fp32 path
+
+def test_c1_tiny_f32_full_parity():
+    w = W.CONFIGS["c1_tiny_f32"]
+    for mode in (BI, CA):
+        outs, ref = _one_shot(w, mode)
+        Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "f32", f"c1 mode={mode}")
+
+
+@pytest.mark.parametrize("mode", [BI, CA])
+@pytest.mark.parametrize("head_dim,dims,page", [(64, (24, 20, 20), 16), (32, (12, 10, 10), 48), (128, (44, 42, 42), 100)])
+def test_f32_cascade_modes(mode, head_dim, dims, page):
+    w = W.small_variant(W.CONFIGS["c1_tiny_f32"], heads=3, grid_h=5, grid_w=7, head_dim=head_dim,
+                        rope_dims=dims, page_tokens=page, n_cached=2, n_inflight=3, max_inflight=3,
+                        window_blocks=2)
+    outs, ref = _one_shot(w, mode, seed=11, first_block=4)
+    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "f32", f"f32 cascade mode={mode}")
+    # peaked softmax: larger logits expose indexing slips that a near-uniform softmax hides
+    outs, ref = _one_shot(w, mode, seed=12, scale=2.5)
+    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "f32", f"f32 peaked mode={mode}")
+
+
+# --------------------------------------------------------------------------- RoPE and cache write
+
+@pytest.mark.parametrize("name", ["c1_tiny_f32", "c3_small"])
+def test_rope3d_apply_matches_oracle(name):
+    import torch
+    if name == "c3_small":
+        w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=5, grid_h=7, grid_w=9)
+    else:
+        w = W.CONFIGS[name]
+    from paper_2511_20426_amd.runner import CascadePool
+    pool = CascadePool.for_workload(w)
+    L, H, D = w.block_tokens, w.heads, w.head_dim
+    n = 2 * L + 17                                     # ragged token count spanning three blocks
+    rng = np.random.default_rng(5)
+    x = W.store(rng.standard_normal((n, 3, H, D), dtype=np.float32), w.dtype)   # packed q/k/v rows
+    first_frame = 3 * w.frames_per_block + 1
+    xt = Hn.to_torch(x, w.dtype)
+    view = xt[:, 1]                                    # strided [n, H, D] view, tok_stride = 3*H*D
+    y = pool.rope(view, first_frame, out=torch.zeros_like(xt)[:, 1])   # same strides as the input view
+    torch.cuda.synchronize()
+    got = Hn.from_torch(y.contiguous(), w.dtype)
+    plane = w.grid_h * w.grid_w
+    idx = np.arange(n)
+    pos = np.stack([first_frame + idx // plane, (idx % plane) // w.grid_w, idx % w.grid_w], axis=1)
+    ref = orc.rope3d(W.to_f64(x[:, 1]), pos, w.rope_dims, w.rope_theta)
+    if w.dtype == "bf16":
+        # one rounding to bf16: half an ulp of the result, plus fp32 rotation error
+        tol = np.abs(ref) * 2.0 ** -8 + 1e-6
+    else:
+        tol = np.abs(ref) * 2.0 ** -22 + 1e-6
+    assert (np.abs(got - ref) <= tol).all(), float(np.abs(got - ref).max())
+    # in place gives the same bits
+    z = view.clone(memory_format=torch.contiguous_format)
+    pool.rope(z, first_frame, out=z)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(Hn.from_torch(z, w.dtype), got)
+
+
+@pytest.mark.parametrize("name", ["c1_tiny_f32", "c3_small"])
+def test_cache_write_pages_bit_exact_layout(name):
+    """Pool bytes after kv_cache_append: V bit-exact, rotated K within one rounding, pad rows zero,
+    each page at the page-pair index the oracle's rule gives."""
+    import torch
+    if name == "c3_small":
+        w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=3, grid_h=7, grid_w=11, sink_blocks=1)
+    else:
+        w = W.CONFIGS[name]
+    from paper_2511_20426_amd.runner import CascadePool
+    pool = CascadePool.for_workload(w)
+    pool.pool.fill_(0xAB)                               # stale bytes must be overwritten, pads zeroed
+    L, H, D, P = w.block_tokens, w.heads, w.head_dim, w.pages_per_block
+    cache = orc.KVCacheOracle(w.sink_blocks, max(w.window_blocks, w.n_cached), w.max_inflight, P, H)
+    rng = np.random.default_rng(9)
+    for g in ((0, 4, 8) if name == "c1_tiny_f32" else (0, 3, 9)):   # three distinct slots
+        k = W.store(rng.standard_normal((L, H, D), dtype=np.float32), w.dtype)
+        v = W.store(rng.standard_normal((L, H, D), dtype=np.float32), w.dtype)
+        slot = pool.append(g, 500, 0, Hn.to_torch(k, w.dtype), Hn.to_torch(v, w.dtype))
+        assert slot == cache.append(g, 500, 0)
+        torch.cuda.synchronize()
+        raw = pool.pool.cpu().numpy()
+        kr = orc.rope3d(W.to_f64(k), orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w),
+                        w.rope_dims, w.rope_theta)
+        for h in range(H):
+            for p in range(P):
+                idx = cache.page_index(slot, p, h)
+                assert idx == pool.ctx.kv_cache_page_index(g, p, h)
+                n0 = p * w.page_tokens
+                nv = min(w.page_tokens, L - n0)
+                if w.dtype == "bf16":
+                    Kp, Vp = Hn.decode_bf16_pages(raw, idx)
+                    np.testing.assert_array_equal(Vp[:nv], v[n0:n0 + nv, h])
+                    Kf = W.bf16_bits_to_f32(Kp).astype(np.float64)
+                    ref = kr[n0:n0 + nv, h]
+                    assert (np.abs(Kf[:nv] - ref) <= np.abs(ref) * 2.0 ** -8 + 1e-6).all()
+                    assert not Kp[nv:].any() and not Vp[nv:].any()
+                else:
+                    Kp, Vp = Hn.decode_f32_pages(raw, idx, w.page_tokens, D)
+                    np.testing.assert_array_equal(Vp[:nv], v[n0:n0 + nv, h])
+                    ref = kr[n0:n0 + nv, h]
+                    assert (np.abs(Kp[:nv] - ref) <= np.abs(ref) * 2.0 ** -22 + 1e-6).all()
+                    assert not Kp[nv:].any() and not Vp[nv:].any()
+
+
+# --------------------------------------------------------------------------- bf16 MFMA path, small shapes
+
+SMALL = [
+    # heads, grid_h, grid_w, n_cached, n_inflight     tokens/block (pages, tail)
+    (3, 10, 13, 2, 3),      # 390  = 3 pages + 6
+    (2, 4, 5, 1, 2),        # 60   : less than one 32-key step of a page is never full
+    (1, 8, 16, 0, 5),       # 384  = exactly 3 pages, no cache at all
+    (5, 13, 11, 3, 1),      # 429  : single in-flight block (cascade P1)
+    (2, 19, 27, 1, 2),      # 1539 : several 256-row tiles per block + ragged rows and keys
+]
+
+
+@pytest.mark.parametrize("mode", [BI, CA])
+@pytest.mark.parametrize("heads,gh,gw,nc,ni", SMALL)
+def test_bf16_small_full_parity(mode, heads, gh, gw, nc, ni):
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=heads, grid_h=gh, grid_w=gw,
+                        n_cached=nc, n_inflight=ni)
+    _say(f"bf16 small heads={heads} grid={gh}x{gw} cached={nc} inflight={ni} mode={mode}")
+    outs, ref = _one_shot(w, mode, seed=21, first_block=2)
+    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", "small")
+    # Peaked softmax (inputs x4: logits x16, V x4) so that a slip on a single key shows.  The
+    # bf16 rounding of rotated Q and K perturbs a logit by about 2^-9 sqrt(2/3) sigma_q sigma_k
+    # = 6e-3 here (4e-4 at the nominal scale), i.e. ~0.6 % on the dominant weights, on top of
+    # the ~0.3 % from rounding P and O; outputs are 4x larger.  Bars scaled accordingly.
+    outs, ref = _one_shot(w, mode, seed=22, scale=2.0)
+    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", "small peaked",
+                    max_abs=0.12, rel=1.2e-2)
+
+
+def test_bf16_single_block_modes_agree_bitwise():
+    """One in-flight block: both modes are the same computation (cascade P1, Fig. 7)."""
+    w = W.small_variant(W.CONFIGS["c2_wan1p3b_seq"], heads=2, grid_h=9, grid_w=14, n_cached=3)
+    q, k, v = W.draw_config(w, seed=31)
+    pool = Hn.gpu_setup(w, k, v, [0, 1, 2], [3])
+    a = Hn.gpu_forward(w, pool, q, [3], BI)
+    b = Hn.gpu_forward(w, pool, q, [3], CA)
+    np.testing.assert_array_equal(a, b)
+
+
+def test_bf16_zero_q_gives_mean_of_visible_v():
+    """Q = 0 -> uniform softmax -> O = mean of visible V; checks the visible key count per mode
+    and that pad keys of the ragged last page do not leak in."""
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=7, grid_w=9, n_cached=2, n_inflight=3)
+    q, k, v = W.draw_config(w, seed=41)
+    q[:] = 0
+    v[:] = W.f32_to_bf16_bits(np.ones(v.shape, np.float32))      # V = 1 -> O = 1 exactly iff weights sum to 1
+    pool = Hn.gpu_setup(w, k, v, [0, 1], [2, 3, 4])
+    for mode in (BI, CA):
+        out = Hn.gpu_forward(w, pool, q, [2, 3, 4], mode)
+        assert np.abs(out - 1.0).max() <= 2.0 ** -8
+    _, _, v2 = W.draw_config(w, seed=42)
+    pool = Hn.gpu_setup(w, k, v2, [0, 1], [2, 3, 4])
+    L = w.block_tokens
+    vf = W.to_f64(v2)
+    for mode in (BI, CA):
+        out = Hn.gpu_forward(w, pool, q, [2, 3, 4], mode)
+        for i in range(3):
+            nb = 2 + (3 if mode == BI else i + 1)
+            mean = vf[:nb * L].mean(axis=0)
+            got = out[i * L:(i + 1) * L]
+            assert np.abs(got - mean[None]).max() <= np.abs(mean).max() * 2.0 ** -7 + 1e-4
+
+
+def test_bf16_deterministic():
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=4, grid_h=12, grid_w=15, n_cached=2, n_inflight=3)
+    q, k, v = W.draw_config(w, seed=51)
+    pool = Hn.gpu_setup(w, k, v, [0, 1], [2, 3, 4])
+    a = Hn.gpu_forward(w, pool, q, [2, 3, 4], BI)
+    b = Hn.gpu_forward(w, pool, q, [2, 3, 4], BI)
+    np.testing.assert_array_equal(a, b)
+
+
+# --------------------------------------------------------------------------- full shapes, sampled rows
+
+def _full_shape(name, modes, heads_sample, n_random):
+    w = W.CONFIGS[name]
+    t0 = time.time()
+    q, k, v = W.draw_config(w)
+    _say(f"{name}: drew inputs in {time.time() - t0:.1f}s")
+    cached = list(range(w.n_cached))
+    infl = list(range(w.n_cached, w.n_cached + w.n_inflight))
+    pool = Hn.gpu_setup(w, k, v, cached, infl, timesteps=list(W.TIMESTEPS[::-1][:len(infl)]))
+    L = w.block_tokens
+    rows = [W.sample_rows(L, n_random, seed=100 + i, tile_edges=(1536,)) for i in range(len(infl))]
+    for mode in modes:
+        t0 = time.time()
+        out = Hn.gpu_forward(w, pool, q, infl, mode)
+        _say(f"{name}: gpu forward mode={mode} done in {time.time() - t0:.1f}s")
+        t0 = time.time()
+        ref = Hn.oracle_forward(w, q, k, v, cached, infl, mode, rows=rows, heads=heads_sample)
+        _say(f"{name}: oracle on {sum(len(r) for r in rows)} rows x {len(heads_sample)} heads in {time.time() - t0:.1f}s")
+        got = [o[np.asarray(r)][:, list(heads_sample)] for o, r in zip(W.split_blocks(out, L), rows)]
+        Hn.assert_close(np.concatenate(got), np.concatenate(ref), "bf16", f"{name} mode={mode}")
+        # property that holds for every row at any size: outputs are convex combinations of V rows
+        assert np.isfinite(out).all()
+        assert np.abs(out).max() <= np.abs(W.bf16_bits_to_f32(v)).max()
+
+
+def test_c2_wan1p3b_sequential_sampled():
+    _full_shape("c2_wan1p3b_seq", [BI], heads_sample=range(12), n_random=16)
+
+
+def test_c3_wan1p3b_cascade_both_modes_sampled():
+    _full_shape("c3_wan1p3b_cascade5", [BI, CA], heads_sample=(0, 5, 11), n_random=12)
+
+
+def test_c4_wan14b_cascade_sampled():
+    _full_shape("c4_wan14b_cascade5", [BI], heads_sample=(0, 1, 17, 39), n_random=8)

@@ -1,0 +1,172 @@
+"""CPU tests of the built library: exported symbols, and the host metadata (slot map, tags,
+visibility, page index) compared bit-exact with the oracle's state machine.  No GPU work:
+contexts are metadata-only (no pool), so nothing is launched.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import cascade_oracle as orc
+from paper_2511_20426_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "cascade_attn.h")).read()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(\w+)\s*\(", body)) - {"defined", "ceil"}
+    declared = {d for d in declared if d.startswith(("ca_", "kv_cache_", "rope3d_", "cascade_"))}
+    assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def _cfg(w: W.Workload, **kw):
+    d = dict(heads=w.heads, head_dim=w.head_dim, frames_per_block=w.frames_per_block, grid_h=w.grid_h,
+             grid_w=w.grid_w, rope_dims=w.rope_dims, rope_theta=w.rope_theta, sink_blocks=w.sink_blocks,
+             window_blocks=w.window_blocks, max_inflight=w.max_inflight, page_tokens=w.page_tokens,
+             dtype=w.dtype)
+    d.update(kw)
+    return B.make_config(**d)
+
+
+def test_pool_bytes():
+    for name, w in W.CONFIGS.items():
+        cfg = _cfg(w)
+        eb = 2 if w.dtype == "bf16" else 4
+        slots = w.sink_blocks + w.window_blocks + w.max_inflight
+        expect = slots * w.pages_per_block * w.heads * 2 * w.page_tokens * w.head_dim * eb
+        assert B.pool_bytes(cfg) == expect, name
+    assert W.CONFIGS["c4_wan14b_cascade5"].pages_per_block == 37
+
+
+def test_config_validation():
+    w = W.CONFIGS["c3_wan1p3b_cascade5"]
+    assert B.pool_bytes(_cfg(w, rope_dims=(44, 42, 40))) == 0          # split does not add up
+    assert B.pool_bytes(_cfg(w, rope_dims=(45, 41, 42))) == 0          # odd split
+    assert B.pool_bytes(_cfg(w, heads=0)) == 0
+    assert B.pool_bytes(_cfg(w, rope_theta=0.0)) == 0
+    assert B.pool_bytes(_cfg(w, max_inflight=0)) == 0
+    with pytest.raises(B.CascadeAttnError) as e:
+        B.Context(_cfg(w, head_dim=64, rope_dims=(24, 20, 20)))        # bf16 needs head_dim 128
+    assert e.value.code == B.CA_EUNSUPPORTED
+    with pytest.raises(B.CascadeAttnError) as e:
+        B.Context(_cfg(w), pool_ptr=0, pool_nbytes=4096)               # pool size without a pool
+    assert e.value.code == B.CA_EINVAL
+    with pytest.raises(B.CascadeAttnError) as e:
+        B.Context(_cfg(w), pool_ptr=4096 + 16, pool_nbytes=1 << 40)    # misaligned pool
+    assert e.value.code == B.CA_EINVAL
+    with pytest.raises(B.CascadeAttnError) as e:
+        B.Context(_cfg(w), pool_ptr=4096, pool_nbytes=1 << 20)         # pool too small
+    assert e.value.code == B.CA_EINVAL
+
+
+def _snap(ctx):
+    return [s.astuple() for s in ctx.kv_cache_snapshot()]
+
+
+def test_rollout_metadata_matches_oracle_bit_exact():
+    """The long-rollout configuration: 40 cascade steps, 1 sink + 6-block window, 5 in flight,
+    prompt switch at step 20.  Slot of every append, snapshot after every phase, visibility
+    matrices and KV order, page indices: all equal to the oracle's."""
+    w = W.CONFIGS["c5_wan1p3b_rollout"]
+    ctx = B.Context(_cfg(w))
+    cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, w.max_inflight, w.pages_per_block, w.heads)
+    epoch = 0
+    evictions = 0
+    for step in range(40):
+        if step == 20:
+            epoch = 1
+            cache.retag(epoch)
+            ctx.kv_cache_retag(epoch)
+            assert _snap(ctx) == cache.snapshot()
+        b, batch = orc.cascade_schedule(step, W.TIMESTEPS, w.max_inflight)
+        slots_lib = [ctx.kv_cache_append(g, t, epoch, 0, 0, 0, 0) for g, t in batch]
+        slots_orc = [cache.append(g, t, epoch) for g, t in batch]
+        assert slots_lib == slots_orc
+        assert _snap(ctx) == cache.snapshot()
+        infl = [g for g, _ in batch]
+        order, states, slots = cache.kv_order(infl)
+        for mode in (B.CA_BIDIRECTIONAL, B.CA_BLOCK_CAUSAL):
+            vis, kv_ids = ctx.debug_visibility(infl, mode)
+            assert kv_ids == order
+            np.testing.assert_array_equal(np.array(vis, dtype=np.uint8),
+                                          orc.visibility(states, order, infl, mode))
+        for g, s in zip(order, slots):
+            for page, head in ((0, 0), (w.pages_per_block - 1, w.heads - 1), (17, 5)):
+                assert ctx.kv_cache_page_index(g, page, head) == cache.page_index(s, page, head)
+        # a forward on a metadata-only context validates and then reports the missing pool
+        with pytest.raises(B.CascadeAttnError) as e:
+            ctx.cascade_attn_forward(0, infl, B.CA_BIDIRECTIONAL, 0)
+        assert e.value.code == B.CA_ENOPOOL
+        if batch[0][1] == 0:
+            ctx.kv_cache_promote(b)
+            cache.promote(b)
+            win = cache.clean_window()
+            if len(win) > w.window_blocks:
+                ctx.kv_cache_evict(win[0])
+                cache.evict(win[0])
+                evictions += 1
+        assert _snap(ctx) == cache.snapshot()
+    assert evictions == 40 - 4 - 7          # first eviction once sink + 6 window blocks are clean
+    snap = _snap(ctx)
+    assert snap[0][:3] == (0, 0, B.CA_SINK)
+    # ring wrapped at least three times
+    assert max(s[1] for s in snap) >= 3 * (w.window_blocks + w.max_inflight)
+
+
+def test_error_paths_leave_state_unchanged():
+    w = W.CONFIGS["c5_wan1p3b_rollout"]
+    ctx = B.Context(_cfg(w, window_blocks=2, max_inflight=2))
+    ctx.kv_cache_append(0, 1000, 0, 0, 0, 0, 0)
+    ctx.kv_cache_append(1, 1000, 0, 0, 0, 0, 0)
+    before = _snap(ctx)
+
+    def fails(code, fn, *a):
+        with pytest.raises(B.CascadeAttnError) as e:
+            fn(*a)
+        assert e.value.code == code, (e.value.code, code)
+        assert _snap(ctx) == before
+
+    fails(B.CA_ENOSPC, ctx.kv_cache_append, 5, 1000, 0, 0, 0, 0, 0)   # ring slot of 5 == slot of 1
+    fails(B.CA_EINVAL, ctx.kv_cache_append, -1, 1000, 0, 0, 0, 0, 0)
+    fails(B.CA_ENOENT, ctx.kv_cache_evict, 7)
+    fails(B.CA_ENOENT, ctx.kv_cache_promote, 3)
+    fails(B.CA_ENOENT, ctx.kv_cache_page_index, 9, 0, 0)
+    fails(B.CA_EINVAL, ctx.kv_cache_page_index, 0, w.pages_per_block, 0)
+    fails(B.CA_EINVAL, ctx.kv_cache_page_index, 0, 0, w.heads)
+    fails(B.CA_ENOENT, ctx.debug_visibility, [0, 2], B.CA_BIDIRECTIONAL)
+    fails(B.CA_EINVAL, ctx.debug_visibility, [1, 0], B.CA_BIDIRECTIONAL)     # not ascending
+    fails(B.CA_EINVAL, ctx.debug_visibility, [0, 1], 7)                      # unknown mode
+    fails(B.CA_EINVAL, ctx.debug_visibility, [], B.CA_BIDIRECTIONAL)
+    fails(B.CA_EINVAL, ctx.debug_visibility, [0, 1, 2], B.CA_BIDIRECTIONAL)  # more than max_inflight
+    fails(B.CA_ENOPOOL, ctx.rope3d_apply, 0, 0, 10, 0, 128, 128)
+    fails(B.CA_EINVAL, ctx.set_kernel_variant, 12345)
+    ctx.kv_cache_promote(0)
+    before = _snap(ctx)
+    assert before[0][2] == B.CA_SINK
+    fails(B.CA_ESTATE, ctx.kv_cache_evict, 0)                # the sink stays
+    fails(B.CA_ESTATE, ctx.kv_cache_promote, 0)
+    fails(B.CA_ESTATE, ctx.kv_cache_append, 0, 0, 0, 0, 0, 0, 0)
+    fails(B.CA_ESTATE, ctx.debug_visibility, [0], B.CA_BIDIRECTIONAL)   # a finished block is not in flight
+    # retag on an empty cache is a no-op that succeeds
+    empty = B.Context(_cfg(w))
+    empty.kv_cache_retag(3)
+    assert _snap(empty) == []
+    assert B.strerror(B.CA_ENOSPC) and B.strerror(-99) == "unknown error"
+
+
+def test_null_context_is_rejected():
+    assert B.lib.kv_cache_promote(None, 0) == B.CA_EINVAL
+    assert B.lib.kv_cache_evict(None, 0) == B.CA_EINVAL
+    assert B.lib.kv_cache_retag(None, 0) == B.CA_EINVAL
+    assert B.lib.ca_destroy(None) == B.CA_EINVAL
+    assert B.lib.ca_pool_bytes(None) == 0
+    n = ctypes.c_int32()
+    assert B.lib.kv_cache_snapshot(None, None, 0, ctypes.byref(n)) == B.CA_EINVAL
