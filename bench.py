@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the block-cascaded attention hot path on one MI355X.
+
+A step is one cascade iteration of one self-attention layer at the Wan-14B shape in steady
+state (6 clean cached blocks + 5 blocks in flight): publish the 5 in-flight blocks' K/V
+(fused K-RoPE + page write), rotate Q, run the cascaded attention, then promote the block
+that completed the cache step, evict the oldest window block and move on by one block.
+Inputs are seeded synthetic N(0,1)*0.5 bf16 tensors already resident in HBM.
+
+Prints ONE JSON line: whole-path TFLOP/s (algorithmic attention flops / step time), the
+roofline of the dominant kernel (attention, MFMA-bound) from its own HIP-event timing, and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6        # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
+
+
+def cpu_baseline(w, seconds_target=15.0):
+    """The fp64 oracle, as it stands, on a bounded sample: a few heads, a slice of query rows
+    of the first in-flight block against all visible keys (K rotation included)."""
+    import numpy as np
+    from oracle import cascade_oracle as orc
+    import workloads as W
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    L, D = w.block_tokens, w.head_dim
+    n_kv_blocks = w.n_cached + w.n_inflight
+    heads, rows = 2, 2048
+    rng = np.random.default_rng(0)
+    total_flops, total_t = 0.0, 0.0
+    pos = lambda g: orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w)
+    kv_g = list(range(n_kv_blocks))
+    g_q = w.n_cached
+    states = [orc.CLEAN] * w.n_cached + [orc.NOISY] * w.n_inflight
+    vis = orc.visibility(states, kv_g, [g_q], orc.BIDIRECTIONAL)
+    for _ in range(16):
+        q = W.store(rng.standard_normal((L, heads, D), dtype=np.float32) * 0.5, "bf16")
+        k = W.store(rng.standard_normal((n_kv_blocks * L, heads, D), dtype=np.float32) * 0.5, "bf16")
+        v = W.store(rng.standard_normal((n_kv_blocks * L, heads, D), dtype=np.float32) * 0.5, "bf16")
+        t0 = time.perf_counter()
+        qb = [orc.rope3d(W.to_f64(q), pos(g_q), w.rope_dims, w.rope_theta)[:rows]]
+        kb = [orc.rope3d(W.to_f64(x), pos(g), w.rope_dims, w.rope_theta)
+              for x, g in zip(W.split_blocks(k, L), kv_g)]
+        vb = [W.to_f64(x) for x in W.split_blocks(v, L)]
+        orc.cascade_attention(qb, kb, vb, vis)
+        total_t += time.perf_counter() - t0
+        total_flops += 4.0 * D * rows * n_kv_blocks * L * heads
+        if total_t >= seconds_target:
+            break
+    return {
+        "value": total_flops / total_t / 1e12, "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+        "sample": f"fp64 numpy oracle, {total_flops / 1e9:.0f} GFLOP of the same shape in {total_t:.1f} s "
+                  f"(query-row slices of one in-flight block x a few heads vs all {n_kv_blocks * L} keys, "
+                  f"K/Q rotation included)",
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c4_wan14b_cascade5")
+    ap.add_argument("--mode", default="bidirectional", choices=["bidirectional", "block_causal"])
+    ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads as W
+    from paper_2511_20426_amd import binding as B
+    from paper_2511_20426_amd.runner import CascadePool
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    w = W.CONFIGS[args.workload]
+    mode = B.CA_BIDIRECTIONAL if args.mode == "bidirectional" else B.CA_BLOCK_CAUSAL
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    L, H, D, C = w.block_tokens, w.heads, w.head_dim, w.n_inflight
+    pool = CascadePool.for_workload(w, device=dev)
+    pool.ctx.set_kernel_variant(args.variant)
+    gen = torch.Generator(device=dev).manual_seed(w.seed)
+    dt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    def draw(n):
+        return (torch.randn((n, H, D), generator=gen, device=dev, dtype=torch.float32) * w.input_scale).to(dt)
+
+    q = draw(C * L)
+    k_blocks = [draw(L) for _ in range(C)]
+    v_blocks = [draw(L) for _ in range(C)]
+    q_rot = torch.empty_like(q)
+    out = torch.empty_like(q)
+
+    # steady-state start: n_cached clean blocks 0..n_cached-1
+    for g in range(w.n_cached):
+        pool.append(g, 0, 0, k_blocks[g % C], v_blocks[g % C])
+        pool.ctx.kv_cache_promote(g)
+    timesteps = list(W.TIMESTEPS[::-1])            # oldest in-flight block is the cleanest (Alg. 1)
+    state = {"b": w.n_cached}
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+          for _ in range(args.steps)]
+
+    def step(i_timed=None):
+        b = state["b"]
+        infl = list(range(b, b + C))
+        for i, g in enumerate(infl):                                   # a1: publish K/V
+            pool.append(g, timesteps[i] if C == len(timesteps) else 0, 0, k_blocks[i], v_blocks[i])
+        pool.rope(q, w.frames_per_block * b, out=q_rot)                # a2
+        if i_timed is not None:
+            ev[i_timed][0].record()
+        pool.forward(q_rot, infl, mode, out=out)                       # a3-a6
+        if i_timed is not None:
+            ev[i_timed][1].record()
+        pool.ctx.kv_cache_promote(b)                                   # a7
+        if w.n_cached > 0:
+            pool.ctx.kv_cache_evict(b - w.n_cached)
+        else:
+            pool.ctx.kv_cache_evict(b)
+        state["b"] = b + 1
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    dt_s = time.perf_counter() - t0
+
+    flops = w.flops(block_causal=(mode == B.CA_BLOCK_CAUSAL))
+    ms_per_step = dt_s / args.steps * 1e3
+    attn_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    achieved = flops / (attn_ms * 1e-3) / 1e12
+    result = {
+        "metric": "cascaded-attn TFLOP/s + % bf16 MFMA peak, Wan-14B shape, 5 in-flight blocks",
+        "value": flops / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "pct_of_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "heads": H, "head_dim": D, "tokens_per_block": L,
+                   "inflight_blocks": C, "cached_blocks": w.n_cached, "mode": args.mode,
+                   "n_q": C * L, "n_kv": (w.n_cached + C) * L, "flops_per_step": flops,
+                   "step": "5x kv_cache_append + rope3d_apply(Q) + cascade_attn_forward + promote/evict"},
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
+                     "avg_launch_ms": attn_ms, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
