@@ -28,8 +28,12 @@ def build(verbose: bool = False, extra=()) -> str:
     objs = []
     bdir = os.path.join(PKG, "_build")
     os.makedirs(bdir, exist_ok=True)
+    # the hand-scheduled attention main loop is emitted as an inline-assembly include
+    subprocess.run([sys.executable, os.path.join(CSRC, "gen_attn_core.py"),
+                    os.path.join(bdir, "attn_core_gfx950.inc")], check=True,
+                   stdout=None if verbose else subprocess.DEVNULL)
     common = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I", os.path.join(ROOT, "include"),
-              "-I", CSRC, "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"] + DEVICE_FLAGS + list(extra)
+              "-I", CSRC, "-I", bdir, "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"] + DEVICE_FLAGS + list(extra)
     procs = []
     for src in SOURCES:
         obj = os.path.join(bdir, src + ".o")

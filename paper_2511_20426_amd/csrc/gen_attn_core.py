@@ -1,0 +1,445 @@
+#!/usr/bin/env python3
+"""Emits attn_core_gfx950.inc: the hand-scheduled main loop of the bf16 cascaded-attention kernel.
+
+The loop is written as one inline-assembly block (included by attn_bf16.hip) because its speed
+rests on two things a compiler will not hold still for:
+
+  * issue order -- a wave issues in order and an MFMA occupies the matrix pipe for 32 cycles, so
+    every MFMA must be followed by ~28 cycles of independent VALU / LDS issue (the softmax of the
+    previous tile, the operand prefetch) instead of by another MFMA;
+  * register files -- Q fragments and the O^T accumulators live in AGPRs, which VALU code never
+    touches in the loop; S^T tiles, P^T and the K/V operand fragments live in VGPRs.
+
+Pipeline (a "step" is 32 keys, a page is 4 steps; t counts steps):
+    QK(t+1): 16 MFMAs  S_next = K_frag x Q                      (K fragments from LDS)
+    SM(t)  : p = exp2(S_cur*c - m_ref), row sums, bf16 pack      (VALU)
+    PV(t-1): 16 MFMAs  O^T   += V_frag x P_prev                  (V fragments from LDS)
+The three are independent inside a step.  K and V pages stream global -> LDS (no registers) into
+two 2-page rings; per page there is one barrier that publishes V(q) and frees V(q-1)'s slot
+(step 1, slot 0) and one that publishes K(q+1) and frees K(q)'s slot (step 2, slot 24).
+
+Register map (fixed):
+  a[0:127]    O^T accumulators, tile (mt, nt) at a[16*(2*mt+nt) ..]
+  a[128:191]  Q fragments, (nt, ks) at a[128 + 4*(8*nt+ks) ..]
+  v[0:31]     S tile A (nt 0: v0.., nt 1: v16..)     v[32:63]  S tile B
+  v[64:79]    P^T tile A, (nt, kk) at v[64 + 4*(2*nt+kk) ..]      v[80:95]  P^T tile B
+  v[96:127]   ring of 8 operand fragments
+  v[128:135]  LDS address of chunk pair j in the K ring, v[136:143] the same in the V ring
+  v144,v145   -m_ref per column tile     v146,v147  m_ref + slack
+  v148..v151  row-sum accumulators (nt, parity of the element)
+  v152..v175  temporaries
+  v176        lane's byte offset inside a page for the page loads
+  v177,v178   per-KV-block page-0 offsets (lane i = block i), low / high word
+  v179        4*(lane/32): first key row this lane holds in a 32x32 accumulator
+  v180        4*(lane ^ 32): ds_bpermute address of the lane holding the other half of this row
+"""
+from __future__ import annotations
+
+import sys
+
+D_AHEAD = 4          # operand fragments are read this many MFMA pairs ahead of use
+PAGE = 32768
+VRING = 65536
+
+# ---------------------------------------------------------------------------- register names
+def V(n, w=1):
+    return f"v{n}" if w == 1 else f"v[{n}:{n + w - 1}]"
+
+
+def A(n, w=1):
+    return f"a{n}" if w == 1 else f"a[{n}:{n + w - 1}]"
+
+
+S_TILE = {"A": 0, "B": 32}
+P_TILE = {"A": 64, "B": 80}
+FR = 96
+XOK, XOV = 128, 136
+NEGM, THR, LACC = 144, 146, 148
+TMP = 152            # 152..175
+T_FMA = [152, 153]
+PX = [154, 155, 156, 157]
+MX = [158, 159]
+RT = list(range(160, 176))     # rare-path temporaries
+VDMA, TBLLO, TBLHI, KIDX, XLANE = 176, 177, 178, 179, 180
+
+# scalar registers (all inside the clobbered range s36..s95)
+S_C, S_NLEFT, S_P, S_PM1, S_STRIDE, S_NKVB = 40, 41, 42, 43, 44, 45
+S_POOL = 46          # 46,47
+S_M0B, S_LASTV = 48, 49
+S_VLAST = 50         # 50..53
+S_PGCUR, S_PGNEXT = 54, 55
+S_KKB, S_KPG, S_VKB, S_VPG = 56, 57, 58, 59
+S_T = 60             # 60..69 temporaries
+S_ADDR = 70          # 70,71
+S_VCC = 72           # 72,73
+S_LDS0 = 74
+
+
+class Emitter:
+    def __init__(self):
+        self.lines = []
+        self.cold = []       # out-of-line blocks, appended after the loop
+        self.uid = 0
+
+    def e(self, s):
+        self.lines.append(s)
+
+    def label(self, stem):
+        self.uid += 1
+        return f"{stem}_{self.uid}_%="
+
+
+# ---------------------------------------------------------------------------- building blocks
+def mfma_qk(first, s_base, nt, frag, ks):
+    d = V(s_base + 16 * nt, 16)
+    c = "0" if first else d
+    return f"v_mfma_f32_32x32x16_bf16 {d}, {V(FR + 4 * (frag % 8), 4)}, {A(128 + 4 * (8 * nt + ks), 4)}, {c}"
+
+
+def mfma_pv(mt, nt, frag, p_base, kk):
+    o = A(16 * (2 * mt + nt), 16)
+    return f"v_mfma_f32_32x32x16_bf16 {o}, {V(FR + 4 * (frag % 8), 4)}, {V(p_base + 4 * (2 * nt + kk), 4)}, {o}"
+
+
+def frag_source(R, par, f):
+    """(address register, immediate) of operand fragment f of step (R, par)."""
+    if f < 8:                                   # K fragment of step t+1
+        if R < 3:
+            return XOK + f, par * PAGE + (R + 1) * 8192
+        return XOK + f, (1 - par) * PAGE        # first step of page q+1
+    g = f - 8
+    mt, kk = g >> 1, g & 1
+    if R == 0:                                  # V of the last step of page q-1
+        return XOV + 6 + kk, (1 - par) * PAGE + mt * 8192
+    return XOV + 2 * (R - 1) + kk, par * PAGE + mt * 8192
+
+
+def ds_read_frag(f, src):
+    reg, imm = src
+    return f"ds_read_b128 {V(FR + 4 * (f % 8), 4)}, {V(reg)} offset:{imm}"
+
+
+def tile_max_ops(s_base):
+    """16 ops leaving max over the 16 accumulator registers of each column tile in MX[nt]."""
+    ops = []
+    for nt in range(2):
+        b = s_base + 16 * nt
+        m = V(MX[nt])
+        ops.append(f"v_max3_f32 {m}, {V(b)}, {V(b + 1)}, {V(b + 2)}")
+        for k in range(6):
+            ops.append(f"v_max3_f32 {m}, {m}, {V(b + 3 + 2 * k)}, {V(b + 4 + 2 * k)}")
+        ops.append(f"v_max_f32 {m}, {m}, {V(b + 15)}")
+    return ops
+
+
+def emit_issue_page(E, which, lds_slot_off, advance):
+    """8 global->LDS loads of the next K (which=0) or V (which=1) page of this wave's share.
+    The (block, page) cursor moves on one page first, staying on the last visible page once the
+    end is reached (the extra copies are never read)."""
+    kb, pg = (S_KKB, S_KPG) if which == 0 else (S_VKB, S_VPG)
+    t = S_T
+    if advance:
+        E.e(f"s_add_u32 s{t}, s{pg}, 1")                         # pg + 1
+        E.e(f"s_cmp_eq_u32 s{t}, s{S_P}")
+        E.e(f"s_cselect_b32 s{t}, 0, s{t}")                      # wrapped page
+        E.e(f"s_addc_u32 s{t + 1}, s{kb}, 0")                    # kb + (wrapped ? 1 : 0): scc still set by cmp
+        E.e(f"s_cmp_lt_u32 s{t + 1}, s{S_NKVB}")                 # still inside the visible blocks?
+        E.e(f"s_cselect_b32 s{pg}, s{t}, s{pg}")
+        E.e(f"s_cselect_b32 s{kb}, s{t + 1}, s{kb}")
+    # 64-bit byte offset: table[kb] + pg*stride + which*PAGE, then + pool base
+    E.e(f"v_readlane_b32 s{t + 2}, {V(TBLLO)}, s{kb}")
+    E.e(f"v_readlane_b32 s{t + 3}, {V(TBLHI)}, s{kb}")
+    E.e(f"s_mul_i32 s{t + 4}, s{pg}, s{S_STRIDE}")
+    E.e(f"s_mul_hi_u32 s{t + 5}, s{pg}, s{S_STRIDE}")
+    E.e(f"s_add_u32 s{t + 2}, s{t + 2}, s{t + 4}")
+    E.e(f"s_addc_u32 s{t + 3}, s{t + 3}, s{t + 5}")
+    if which:
+        E.e(f"s_add_u32 s{t + 2}, s{t + 2}, {PAGE}")
+        E.e(f"s_addc_u32 s{t + 3}, s{t + 3}, 0")
+    E.e(f"s_add_u32 s{S_ADDR}, s{S_POOL}, s{t + 2}")
+    E.e(f"s_addc_u32 s{S_ADDR + 1}, s{S_POOL + 1}, s{t + 3}")
+    E.e(f"s_add_u32 s{t + 6}, s{S_M0B}, {lds_slot_off}")
+    for i in range(8):
+        E.e(f"s_mov_b32 m0, s{t + 6}")
+        E.e(f"global_load_lds_dwordx4 {V(VDMA)}, s[{S_ADDR}:{S_ADDR + 1}]")
+        if i < 7:
+            E.e(f"s_add_u32 s{S_ADDR}, s{S_ADDR}, 4096")
+            E.e(f"s_addc_u32 s{S_ADDR + 1}, s{S_ADDR + 1}, 0")
+            E.e(f"s_add_u32 s{t + 6}, s{t + 6}, 4096")
+
+
+def emit_mask(E, s_base, valid_sreg):
+    """Scores of keys at or past `valid` (keys of this 32-key step) become -inf, both column tiles."""
+    E.e(f"v_mov_b32 {V(RT[0])}, 0xff800000")
+    for i in range(16):
+        const = 8 * (i >> 2) + (i & 3)
+        E.e(f"s_sub_i32 s{S_T}, s{valid_sreg}, {const}")
+        E.e(f"v_cmp_lt_i32 vcc, {V(KIDX)}, s{S_T}")                 # key row < valid
+        for nt in range(2):
+            r = V(s_base + 16 * nt + i)
+            E.e(f"v_cndmask_b32 {r}, {V(RT[0])}, {r}, vcc")
+
+
+def emit_settle(E, s_base, p_wait_base):
+    """Reference update for the S tile at s_base (max in MX): if some score exceeds m_ref + slack,
+    move the reference, rescale row sums, accumulators and the P tile still waiting for its PV."""
+    cold, back = E.label("RARE"), E.label("BACK")
+    E.e(f"v_mul_f32 {V(RT[0])}, s{S_C}, {V(MX[0])}")
+    E.e(f"v_mul_f32 {V(RT[1])}, s{S_C}, {V(MX[1])}")
+    E.e(f"v_cmp_gt_f32 vcc, {V(RT[0])}, {V(THR)}")
+    E.e(f"s_mov_b64 s[{S_VCC}:{S_VCC + 1}], vcc")
+    E.e(f"v_cmp_gt_f32 vcc, {V(RT[1])}, {V(THR + 1)}")
+    E.e(f"s_or_b64 vcc, vcc, s[{S_VCC}:{S_VCC + 1}]")
+    E.e(f"s_cbranch_vccnz {cold}")
+    E.e(f"{back}:")
+    c = E.cold
+    c.append(f"{cold}:")
+    c.append("s_nop 15\ns_nop 15\ns_nop 15")            # every MFMA issued so far has written back
+    for nt in range(2):
+        t, a_, b_, mnew, d, alpha = (V(RT[nt]), V(RT[2]), V(RT[3]), V(RT[4]), V(RT[5]), V(RT[6]))
+        c.append(f"ds_bpermute_b32 {b_}, {V(XLANE)}, {t}")          # the partner lane's (lane ^ 32) maximum
+        c.append("s_waitcnt lgkmcnt(0)")
+        c.append(f"v_max_f32 {a_}, {t}, {b_}")
+        c.append(f"v_max_f32 {mnew}, {a_}, -{V(NEGM + nt)}")          # max(m_ref, tile max)
+        c.append(f"v_add_f32 {d}, {V(NEGM + nt)}, {mnew}")            # m_new - m_ref  (>= 0, +inf at start)
+        c.append(f"v_exp_f32_e64 {alpha}, -{d}")
+        c.append("s_nop 3")                              # a trans result is not forwarded to the next VALU op
+        c.append(f"v_mul_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {alpha}")
+        c.append(f"v_mul_f32 {V(LACC + 2 * nt + 1)}, {V(LACC + 2 * nt + 1)}, {alpha}")
+        for mt in range(4):
+            for i in range(16):
+                acc = A(16 * (2 * mt + nt) + i)
+                tmp = V(RT[8 + (i % 8)])
+                c.append(f"v_accvgpr_read_b32 {tmp}, {acc}")
+                c.append(f"v_mul_f32 {tmp}, {tmp}, {alpha}")
+                c.append(f"v_accvgpr_write_b32 {acc}, {tmp}")
+        for kk in range(2):
+            for w in range(4):
+                r = V(p_wait_base + 4 * (2 * nt + kk) + w)
+                lo, hi = V(RT[8]), V(RT[9])
+                c.append(f"v_lshlrev_b32 {lo}, 16, {r}")
+                c.append(f"v_and_b32 {hi}, 0xffff0000, {r}")
+                c.append(f"v_mul_f32 {lo}, {lo}, {alpha}")
+                c.append(f"v_mul_f32 {hi}, {hi}, {alpha}")
+                c.append(f"v_cvt_pk_bf16_f32 {r}, {lo}, {hi}")
+        c.append(f"v_mul_f32 {V(NEGM + nt)}, -1.0, {mnew}")
+        c.append(f"v_add_f32 {V(THR + nt)}, 8.0, {mnew}")
+    c.append("s_nop 7")
+    c.append(f"s_branch {back}")
+
+
+def emit_mask_check(E, s_base, pg_sreg, sub):
+    """If the tile at s_base is the ragged tail of a block's last page: mask it and redo its max."""
+    cold, back = E.label("MASK"), E.label("MBACK")
+    E.e(f"s_cmp_eq_u32 s{pg_sreg}, s{S_PM1}")
+    E.e(f"s_cselect_b32 s{S_T + 8}, s{S_VLAST + sub}, 32")
+    E.e(f"s_cmp_lt_u32 s{S_T + 8}, 32")
+    E.e(f"s_cbranch_scc1 {cold}")
+    E.e(f"{back}:")
+    sub_e = Emitter()
+    sub_e.uid = E.uid
+    emit_mask(sub_e, s_base, S_T + 8)
+    E.cold.append(f"{cold}:")
+    E.cold.append("s_nop 15\ns_nop 15\ns_nop 15")
+    E.cold.extend(sub_e.lines)
+    E.cold.extend(tile_max_ops(s_base))
+    E.cold.append(f"s_branch {back}")
+
+
+def emit_step(E, R, par):
+    cur, nxt = ("A", "B") if R % 2 == 0 else ("B", "A")
+    s_cur, s_next = S_TILE[cur], S_TILE[nxt]
+    p_prev, p_cur = (P_TILE["B"], P_TILE["A"]) if R % 2 == 0 else (P_TILE["A"], P_TILE["B"])
+    nR, npar = ((R + 1) & 3, par if R < 3 else 1 - par)
+    max_ops = tile_max_ops(s_next)
+    max_at = {}                                           # slot -> ops (slots 20..31)
+    for k, op in enumerate(max_ops):
+        max_at.setdefault(20 + (k * 12) // 16, []).append(op)
+
+    E.e(f"; ---- step R={R} parity={par}")
+    for i in range(32):
+        f, nt = i >> 1, i & 1
+        if R == 1 and i == 0:                             # V(q) visible; slot of V(q-1) free -> V(q+1)
+            E.e("s_waitcnt vmcnt(8)")
+            E.e("s_barrier")
+            emit_issue_page(E, 1, VRING + (1 - par) * PAGE, advance=True)
+        if R == 2 and i == 24:                            # K(q+1) visible; slot of K(q) free -> K(q+2)
+            E.e("s_waitcnt vmcnt(8)")
+            E.e("s_barrier")
+            emit_issue_page(E, 0, par * PAGE, advance=True)
+        if nt == 0:
+            E.e(f"s_waitcnt lgkmcnt({D_AHEAD - 1})")      # fragment f has landed
+        if f < 8:
+            E.e(mfma_qk(f == 0, s_next, nt, f, f))
+        else:
+            g = f - 8
+            E.e(mfma_pv(g >> 1, nt, f, p_prev, g & 1))
+        # fillers: operand prefetch, softmax of s_cur, running max of s_next
+        if nt == 0:
+            fa = f + D_AHEAD
+            if fa < 16:
+                E.e(ds_read_frag(fa, frag_source(R, par, fa)))
+            else:
+                E.e(ds_read_frag(fa - 16, frag_source(nR, npar, fa - 16)))
+        ent, ee = i >> 4, i & 15
+        E.e(f"v_fma_f32 {V(T_FMA[i & 1])}, {V(s_cur + 16 * ent + ee)}, s{S_C}, {V(NEGM + ent)}")
+        # A trans result is consumed two slots later: on gfx950 a VALU op that reads a v_exp
+        # result only a couple of issue slots after it saw stale data in half of the lanes.
+        if i >= 2:
+            emit_finish_element(E, i - 2, p_cur)
+        E.e(f"v_exp_f32 {V(PX[i & 3])}, {V(T_FMA[i & 1])}")
+        for op in max_at.get(i, []):
+            E.e(op)
+    E.e("s_nop 3")
+    emit_finish_element(E, 30, p_cur)
+    emit_finish_element(E, 31, p_cur)
+    # the tile just produced is exponentiated in the next step: mask its ragged tail, settle m_ref
+    if R < 3:
+        emit_mask_check(E, s_next, S_PGCUR, R + 1)
+    else:
+        emit_mask_check(E, s_next, S_PGNEXT, 0)
+    emit_settle(E, s_next, p_cur)
+
+
+def emit_finish_element(E, j, p_cur):
+    nt, e = j >> 4, j & 15
+    E.e(f"v_add_f32 {V(LACC + 2 * nt + (e & 1))}, {V(LACC + 2 * nt + (e & 1))}, {V(PX[j & 3])}")
+    if e & 1:
+        dst = V(p_cur + 4 * (2 * nt + (e >> 3)) + ((e & 7) >> 1))
+        E.e(f"v_cvt_pk_bf16_f32 {dst}, {V(PX[(j - 1) & 3])}, {V(PX[j & 3])}")
+
+
+def emit_page_end(E):
+    """Per-page scalar bookkeeping: page-in-block counters of pages q and q+1."""
+    E.e(f"s_mov_b32 s{S_PGCUR}, s{S_PGNEXT}")
+    E.e(f"s_add_u32 s{S_T}, s{S_PGNEXT}, 1")
+    E.e(f"s_cmp_eq_u32 s{S_T}, s{S_P}")
+    E.e(f"s_cselect_b32 s{S_PGNEXT}, 0, s{S_T}")
+
+
+def emit_drain(E, par_last):
+    """PV of the final step: V page (parity par_last), keys 96..127, P tile B."""
+    for g in range(8):
+        mt, kk = g >> 1, g & 1
+        E.e(f"ds_read_b128 {V(FR + 4 * g, 4)}, {V(XOV + 6 + kk)} offset:{par_last * PAGE + mt * 8192}")
+    E.e("s_waitcnt lgkmcnt(0)")
+    for g in range(8):
+        for nt in range(2):
+            E.e(mfma_pv(g >> 1, nt, g, P_TILE["B"], g & 1))
+
+
+def generate():
+    E = Emitter()
+    # ---- set-up: inputs to fixed registers
+    E.e(f"s_mov_b32 s{S_C}, %[c]")
+    E.e(f"s_mov_b32 s{S_NLEFT}, %[n_pages]")
+    E.e(f"s_mov_b32 s{S_P}, %[ppb]")
+    E.e(f"s_sub_u32 s{S_PM1}, s{S_P}, 1")
+    E.e(f"s_mov_b32 s{S_STRIDE}, %[stride]")
+    E.e(f"s_mov_b32 s{S_NKVB}, %[n_kvb]")
+    E.e(f"s_mov_b64 s[{S_POOL}:{S_POOL + 1}], %[pool]")
+    E.e(f"s_mov_b32 s{S_LDS0}, %[lds0]")
+    E.e(f"s_lshl_b32 s{S_M0B}, %[wave], 10")
+    E.e(f"s_add_u32 s{S_M0B}, s{S_M0B}, s{S_LDS0}")
+    E.e(f"s_mov_b32 s{S_LASTV}, %[last_valid]")
+    for sub in range(4):                                  # clamp(last_valid - 32*sub, 0, 32)
+        E.e(f"s_sub_i32 s{S_VLAST + sub}, s{S_LASTV}, {32 * sub}")
+        E.e(f"s_max_i32 s{S_VLAST + sub}, s{S_VLAST + sub}, 0")
+        E.e(f"s_min_i32 s{S_VLAST + sub}, s{S_VLAST + sub}, 32")
+    E.e(f"v_mov_b32 {V(VDMA)}, %[lane_off]")
+    E.e(f"v_mov_b32 {V(TBLLO)}, %[tbl_lo]")
+    E.e(f"v_mov_b32 {V(TBLHI)}, %[tbl_hi]")
+    E.e(f"v_mov_b32 {V(KIDX)}, %[kidx]")
+    E.e(f"v_mov_b32 {V(XLANE)}, %[xlane]")
+    for j in range(8):
+        E.e(f"v_xor_b32 {V(XOK + j)}, {j << 5}, %[xo0]")
+        E.e(f"v_add_u32 {V(XOK + j)}, s{S_LDS0}, {V(XOK + j)}")
+        E.e(f"v_add_u32 {V(XOV + j)}, {VRING}, {V(XOK + j)}")
+    for r in range(128):
+        E.e(f"v_accvgpr_write_b32 {A(r)}, 0")
+    for r in range(4):
+        E.e(f"v_mov_b32 {V(LACC + r)}, 0")
+    for nt in range(2):
+        E.e(f"v_mov_b32 {V(NEGM + nt)}, 0x7f800000")      # -m_ref = +inf
+        E.e(f"v_mov_b32 {V(THR + nt)}, 0xff800000")       # m_ref + slack = -inf
+    for r in range(16):
+        E.e(f"v_mov_b32 {V(P_TILE['B'] + r)}, 0")
+    E.e(f"s_mov_b32 s{S_PGCUR}, 0")
+    E.e(f"s_cmp_eq_u32 s{S_P}, 1")
+    E.e(f"s_cselect_b32 s{S_PGNEXT}, 0, 1")
+    for r in (S_KKB, S_KPG, S_VKB, S_VPG):
+        E.e(f"s_mov_b32 s{r}, 0")
+    # ---- K(0), V(0), K(1) in flight; wait for the first two, publish
+    emit_issue_page(E, 0, 0, advance=False)
+    emit_issue_page(E, 1, VRING, advance=False)
+    emit_issue_page(E, 0, PAGE, advance=True)
+    E.e("s_waitcnt vmcnt(8) lgkmcnt(0)")
+    E.e("s_barrier")
+    # ---- S tile of step 0 into tile A, its mask, max and reference
+    for f in range(8):
+        E.e(f"ds_read_b128 {V(FR + 4 * f, 4)}, {V(XOK + f)} offset:0")
+    E.e("s_waitcnt lgkmcnt(0)")
+    for f in range(8):
+        for nt in range(2):
+            E.e(mfma_qk(f == 0, S_TILE["A"], nt, f, f))
+    E.e("s_nop 15\ns_nop 15\ns_nop 15")
+    for op in tile_max_ops(S_TILE["A"]):
+        E.e(op)
+    emit_mask_check(E, S_TILE["A"], S_PGCUR, 0)
+    emit_settle(E, S_TILE["A"], P_TILE["B"])
+    # first operand fragments of step (R=0, parity 0)
+    for f in range(D_AHEAD):
+        E.e(ds_read_frag(f, frag_source(0, 0, f)))
+
+    # ---- main loop, two pages per trip (ring parity is compile-time)
+    loop, exit_even, exit_odd, done = (E.label("LOOP"), E.label("EXIT_EVEN"), E.label("EXIT_ODD"),
+                                        E.label("DONE"))
+    E.e(f"{loop}:")
+    for par in range(2):
+        for R in range(4):
+            emit_step(E, R, par)
+        emit_page_end(E)
+        E.e(f"s_sub_u32 s{S_NLEFT}, s{S_NLEFT}, 1")
+        E.e(f"s_cmp_eq_u32 s{S_NLEFT}, 0")
+        E.e(f"s_cbranch_scc1 {exit_even if par == 0 else exit_odd}")
+    E.e(f"s_branch {loop}")
+    E.e(f"{exit_even}:")
+    E.e("s_waitcnt lgkmcnt(0)")
+    emit_drain(E, 0)
+    E.e(f"s_branch {done}")
+    E.e(f"{exit_odd}:")
+    E.e("s_waitcnt lgkmcnt(0)")
+    emit_drain(E, 1)
+    E.e(f"s_branch {done}")
+    # ---- out-of-line blocks
+    for ln in E.cold:
+        E.e(ln)
+    E.e(f"{done}:")
+    E.e("s_waitcnt vmcnt(0)")                              # trailing (unused) page loads have landed
+    E.e("s_nop 15\ns_nop 15\ns_nop 15")                    # the last MFMAs have written back
+    return E.lines
+
+
+def main(out_path):
+    lines = generate()
+    text = []
+    for ln in lines:
+        for part in ln.split("\n"):
+            text.append(part)
+    with open(out_path, "w") as f:
+        f.write("// Generated by gen_attn_core.py -- do not edit.\n")
+        for t in text:
+            f.write('"' + t.replace("\\", "\\\\").replace('"', '\\"') + '\\n"\n')
+    # registers the block uses beyond its operands (v148..v151 are outputs)
+    clob = [f"v{i}" for i in range(0, 200) if not 144 <= i <= 151 or i in (146, 147)] + [f"s{i}" for i in range(36, 96)]
+    clob_path = out_path.replace("attn_core_gfx950.inc", "attn_core_clobbers.inc")
+    with open(clob_path, "w") as f:
+        f.write("// Generated by gen_attn_core.py -- do not edit.\n#define CA_CORE_CLOBBERS \\\n")
+        for i in range(0, len(clob), 12):
+            chunk = ", ".join(f'"{c}"' for c in clob[i:i + 12])
+            f.write("  " + chunk + (", \\\n" if i + 12 < len(clob) else "\n"))
+    print(f"{out_path}: {len(text)} lines")
+
+
+if __name__ == "__main__":
+    main(sys.argv[1] if len(sys.argv) > 1 else "attn_core_gfx950.inc")
