@@ -9,7 +9,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
-LIB = os.path.join(PKG, "libcascade_attn.so")
+LIB = os.environ.get("CASCADE_ATTN_LIB") or os.path.join(PKG, "libcascade_attn.so")
 
 SOURCES = ["ca_meta.cpp", "ca_api.cpp", "rope_cache.hip", "attn_f32.hip", "attn_bf16.hip"]
 

@@ -14,7 +14,7 @@ from dataclasses import dataclass
 from typing import List, Optional, Sequence, Tuple
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libcascade_attn.so")
+LIB_PATH = os.environ.get("CASCADE_ATTN_LIB") or os.path.join(_PKG, "libcascade_attn.so")
 
 CA_OK, CA_EINVAL, CA_ENOSPC, CA_ENOENT, CA_ESTATE, CA_EUNSUPPORTED, CA_ENOPOOL, CA_EDEVICE = (
     0, -1, -2, -3, -4, -5, -6, -7)

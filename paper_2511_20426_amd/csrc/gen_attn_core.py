@@ -12,7 +12,8 @@ rests on two things a compiler will not hold still for:
 
 Pipeline (a "step" is 32 keys, a page is 4 steps; t counts steps):
     QK(t+1): 16 MFMAs  S_next = K_frag x Q                      (K fragments from LDS)
-    SM(t)  : p = exp2(S_cur*c - m_ref), row sums, bf16 pack      (VALU)
+    SM(t)  : p = exp2(S_cur), bf16 pack, row sums                (VALU; S_cur already holds
+             s*c - m_ref: Q is pre-scaled by c = log2(e)/sqrt(D) and QK starts from -m_ref)
     PV(t-1): 16 MFMAs  O^T   += V_frag x P_prev                  (V fragments from LDS)
 The three are independent inside a step.  K and V pages stream global -> LDS (no registers) into
 two 2-page rings; per page there is one barrier that publishes V(q) and frees V(q-1)'s slot
@@ -25,17 +26,24 @@ Register map (fixed):
   v[64:79]    P^T tile A, (nt, kk) at v[64 + 4*(2*nt+kk) ..]      v[80:95]  P^T tile B
   v[96:127]   ring of 8 operand fragments
   v[128:135]  LDS address of chunk pair j in the K ring, v[136:143] the same in the V ring
-  v144,v145   -m_ref per column tile     v146,v147  m_ref + slack
-  v148..v151  row-sum accumulators (nt, parity of the element)
+  v148..v151  row-sum accumulators (nt, parity of the packed pair)
+  v[184:199], v[200:215]  -m_ref of column tile 0 / 1, replicated 16 times: the C operand of the
+              first MFMA of every S tile, so a tile comes out of the matrix pipe as s*c - m_ref
   v152..v175  temporaries
-  v176        lane's byte offset inside a page for the page loads
+  v[216:223]  lane's byte offset inside a page for page load i = 0..7
   v177,v178   per-KV-block page-0 offsets (lane i = block i), low / high word
   v179        4*(lane/32): first key row this lane holds in a 32x32 accumulator
   v180        4*(lane ^ 32): ds_bpermute address of the lane holding the other half of this row
 """
 from __future__ import annotations
 
+import os
 import sys
+
+# Timing experiments only (CA_ABL in the environment of the build): switch parts of the loop off.
+# 1 no softmax arithmetic, 2 no LDS operand reads, 4 no page loads, 8 no barriers.  Results are
+# then meaningless; the shipped library is always built with 0.
+ABL = int(os.environ.get("CA_ABL", "0"))
 
 D_AHEAD = 4          # operand fragments are read this many MFMA pairs ahead of use
 PAGE = 32768
@@ -54,13 +62,15 @@ S_TILE = {"A": 0, "B": 32}
 P_TILE = {"A": 64, "B": 80}
 FR = 96
 XOK, XOV = 128, 136
-NEGM, THR, LACC = 144, 146, 148
+LACC = 148
+NT = [184, 200]      # -m_ref replicated 16x per column tile
 TMP = 152            # 152..175
 T_FMA = [152, 153]
 PX = [154, 155, 156, 157]
 MX = [158, 159]
 RT = list(range(160, 176))     # rare-path temporaries
-VDMA, TBLLO, TBLHI, KIDX, XLANE = 176, 177, 178, 179, 180
+TBLLO, TBLHI, KIDX, XLANE = 177, 178, 179, 180
+DMAOFF = 216         # 216..223: lane's byte offset in a page for load i (+4096 i)
 
 # scalar registers (all inside the clobbered range s36..s95)
 S_C, S_NLEFT, S_P, S_PM1, S_STRIDE, S_NKVB = 40, 41, 42, 43, 44, 45
@@ -73,6 +83,7 @@ S_T = 60             # 60..69 temporaries
 S_ADDR = 70          # 70,71
 S_VCC = 72           # 72,73
 S_LDS0 = 74
+S_ONES = 75          # bf16 pair (1.0, 1.0)
 
 
 class Emitter:
@@ -92,7 +103,7 @@ class Emitter:
 # ---------------------------------------------------------------------------- building blocks
 def mfma_qk(first, s_base, nt, frag, ks):
     d = V(s_base + 16 * nt, 16)
-    c = "0" if first else d
+    c = V(NT[nt], 16) if first else d
     return f"v_mfma_f32_32x32x16_bf16 {d}, {V(FR + 4 * (frag % 8), 4)}, {A(128 + 4 * (8 * nt + ks), 4)}, {c}"
 
 
@@ -108,7 +119,7 @@ def frag_source(R, par, f):
             return XOK + f, par * PAGE + (R + 1) * 8192
         return XOK + f, (1 - par) * PAGE        # first step of page q+1
     g = f - 8
-    mt, kk = g >> 1, g & 1
+    mt, kk = g & 3, g >> 2                      # an accumulator tile is revisited 8 MFMAs later
     if R == 0:                                  # V of the last step of page q-1
         return XOV + 6 + kk, (1 - par) * PAGE + mt * 8192
     return XOV + 2 * (R - 1) + kk, par * PAGE + mt * 8192
@@ -132,10 +143,10 @@ def tile_max_ops(s_base):
     return ops
 
 
-def emit_issue_page(E, which, lds_slot_off, advance):
-    """8 global->LDS loads of the next K (which=0) or V (which=1) page of this wave's share.
-    The (block, page) cursor moves on one page first, staying on the last visible page once the
-    end is reached (the extra copies are never read)."""
+def emit_page_address(E, which, advance):
+    """Scalar part of a page request: move the (block, page) cursor of the K (which=0) or V
+    (which=1) stream on by one page -- staying on the last visible page once the end is reached
+    (the extra copies are never read) -- and leave the page's global address in s[S_ADDR:+1]."""
     kb, pg = (S_KKB, S_KPG) if which == 0 else (S_VKB, S_VPG)
     t = S_T
     if advance:
@@ -158,14 +169,20 @@ def emit_issue_page(E, which, lds_slot_off, advance):
         E.e(f"s_addc_u32 s{t + 3}, s{t + 3}, 0")
     E.e(f"s_add_u32 s{S_ADDR}, s{S_POOL}, s{t + 2}")
     E.e(f"s_addc_u32 s{S_ADDR + 1}, s{S_POOL + 1}, s{t + 3}")
-    E.e(f"s_add_u32 s{t + 6}, s{S_M0B}, {lds_slot_off}")
+
+
+def emit_page_load(E, i, lds_slot_off):
+    """Load number i (0..7) of the requested page: 64 lanes x 16 B -> 1 KB of LDS at
+    slot + 4096 i + 1024 wave (M0 carries the LDS address, the VGPR the byte offset in the page)."""
+    E.e(f"s_add_u32 m0, s{S_M0B}, {lds_slot_off + 4096 * i}")
+    if not ABL & 4:
+        E.e(f"global_load_lds_dwordx4 {V(DMAOFF + i)}, s[{S_ADDR}:{S_ADDR + 1}]")
+
+
+def emit_issue_page(E, which, lds_slot_off, advance):
+    emit_page_address(E, which, advance)
     for i in range(8):
-        E.e(f"s_mov_b32 m0, s{t + 6}")
-        E.e(f"global_load_lds_dwordx4 {V(VDMA)}, s[{S_ADDR}:{S_ADDR + 1}]")
-        if i < 7:
-            E.e(f"s_add_u32 s{S_ADDR}, s{S_ADDR}, 4096")
-            E.e(f"s_addc_u32 s{S_ADDR + 1}, s{S_ADDR + 1}, 0")
-            E.e(f"s_add_u32 s{t + 6}, s{t + 6}, 4096")
+        emit_page_load(E, i, lds_slot_off)
 
 
 def emit_mask(E, s_base, valid_sreg):
@@ -180,32 +197,35 @@ def emit_mask(E, s_base, valid_sreg):
             E.e(f"v_cndmask_b32 {r}, {V(RT[0])}, {r}, vcc")
 
 
-def emit_settle(E, s_base, p_wait_base):
-    """Reference update for the S tile at s_base (max in MX): if some score exceeds m_ref + slack,
-    move the reference, rescale row sums, accumulators and the P tile still waiting for its PV."""
+def emit_settle(E, s_base, p_wait_base, first=False):
+    """Reference update for the S tile at s_base (its maximum, relative to the current m_ref, is in
+    MX): if some score exceeds m_ref by more than the slack, m_ref moves up to the row maximum and
+    everything formed against the old reference is rescaled: row sums, accumulators, the P tile
+    still waiting for its PV product, and this S tile itself.  first=True: unconditional (tile 0)."""
     cold, back = E.label("RARE"), E.label("BACK")
-    E.e(f"v_mul_f32 {V(RT[0])}, s{S_C}, {V(MX[0])}")
-    E.e(f"v_mul_f32 {V(RT[1])}, s{S_C}, {V(MX[1])}")
-    E.e(f"v_cmp_gt_f32 vcc, {V(RT[0])}, {V(THR)}")
-    E.e(f"s_mov_b64 s[{S_VCC}:{S_VCC + 1}], vcc")
-    E.e(f"v_cmp_gt_f32 vcc, {V(RT[1])}, {V(THR + 1)}")
-    E.e(f"s_or_b64 vcc, vcc, s[{S_VCC}:{S_VCC + 1}]")
-    E.e(f"s_cbranch_vccnz {cold}")
+    if first:
+        E.e(f"s_branch {cold}")
+    else:
+        E.e(f"v_cmp_lt_f32 vcc, 0x41000000, {V(MX[0])}")           # 8.0 < max
+        E.e(f"s_mov_b64 s[{S_VCC}:{S_VCC + 1}], vcc")
+        E.e(f"v_cmp_lt_f32 vcc, 0x41000000, {V(MX[1])}")
+        E.e(f"s_or_b64 vcc, vcc, s[{S_VCC}:{S_VCC + 1}]")
+        E.e(f"s_cbranch_vccnz {cold}")
     E.e(f"{back}:")
     c = E.cold
     c.append(f"{cold}:")
     c.append("s_nop 15\ns_nop 15\ns_nop 15")            # every MFMA issued so far has written back
     for nt in range(2):
-        t, a_, b_, mnew, d, alpha = (V(RT[nt]), V(RT[2]), V(RT[3]), V(RT[4]), V(RT[5]), V(RT[6]))
-        c.append(f"ds_bpermute_b32 {b_}, {V(XLANE)}, {t}")          # the partner lane's (lane ^ 32) maximum
+        t, other, delta, alpha = V(MX[nt]), V(RT[3]), V(RT[4]), V(RT[6])
+        c.append(f"ds_bpermute_b32 {other}, {V(XLANE)}, {t}")        # the partner lane's (lane ^ 32) maximum
         c.append("s_waitcnt lgkmcnt(0)")
-        c.append(f"v_max_f32 {a_}, {t}, {b_}")
-        c.append(f"v_max_f32 {mnew}, {a_}, -{V(NEGM + nt)}")          # max(m_ref, tile max)
-        c.append(f"v_add_f32 {d}, {V(NEGM + nt)}, {mnew}")            # m_new - m_ref  (>= 0, +inf at start)
-        c.append(f"v_exp_f32_e64 {alpha}, -{d}")
+        c.append(f"v_max_f32 {delta}, {t}, {other}")
+        if not first:
+            c.append(f"v_max_f32 {delta}, 0, {delta}")               # the reference never moves down
+        c.append(f"v_exp_f32_e64 {alpha}, -{delta}")
         c.append("s_nop 3")                              # a trans result is not forwarded to the next VALU op
-        c.append(f"v_mul_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {alpha}")
-        c.append(f"v_mul_f32 {V(LACC + 2 * nt + 1)}, {V(LACC + 2 * nt + 1)}, {alpha}")
+        for k in range(2):
+            c.append(f"v_mul_f32 {V(LACC + 2 * nt + k)}, {V(LACC + 2 * nt + k)}, {alpha}")
         for mt in range(4):
             for i in range(16):
                 acc = A(16 * (2 * mt + nt) + i)
@@ -222,8 +242,9 @@ def emit_settle(E, s_base, p_wait_base):
                 c.append(f"v_mul_f32 {lo}, {lo}, {alpha}")
                 c.append(f"v_mul_f32 {hi}, {hi}, {alpha}")
                 c.append(f"v_cvt_pk_bf16_f32 {r}, {lo}, {hi}")
-        c.append(f"v_mul_f32 {V(NEGM + nt)}, -1.0, {mnew}")
-        c.append(f"v_add_f32 {V(THR + nt)}, 8.0, {mnew}")
+        for i in range(16):                              # -m_ref operand and the tile itself
+            c.append(f"v_sub_f32 {V(NT[nt] + i)}, {V(NT[nt] + i)}, {delta}")
+            c.append(f"v_sub_f32 {V(s_base + 16 * nt + i)}, {V(s_base + 16 * nt + i)}, {delta}")
     c.append("s_nop 7")
     c.append(f"s_branch {back}")
 
@@ -237,13 +258,37 @@ def emit_mask_check(E, s_base, pg_sreg, sub):
     E.e(f"s_cbranch_scc1 {cold}")
     E.e(f"{back}:")
     sub_e = Emitter()
-    sub_e.uid = E.uid
     emit_mask(sub_e, s_base, S_T + 8)
     E.cold.append(f"{cold}:")
     E.cold.append("s_nop 15\ns_nop 15\ns_nop 15")
     E.cold.extend(sub_e.lines)
     E.cold.extend(tile_max_ops(s_base))
     E.cold.append(f"s_branch {back}")
+
+
+def p_word(p_base, j):
+    """VGPR of the packed pair that ends at element j (odd) of the tile being exponentiated."""
+    nt, e = j >> 4, j & 15
+    return p_base + 4 * (2 * nt + (e >> 3)) + ((e & 7) >> 1)
+
+
+def emit_pack(E, j, p_cur):
+    """elements j-1, j -> one bf16 pair of P^T (round to nearest even)."""
+    E.e(f"v_cvt_pk_bf16_f32 {V(p_word(p_cur, j))}, {V(PX[(j - 1) & 3])}, {V(PX[j & 3])}")
+
+
+ROWSUM = os.environ.get("CA_ROWSUM", "add")     # v_dot2_f32_bf16 on the packed pair measured 2.3 ms slower per forward
+
+
+def emit_rowsum(E, j, p_cur):
+    """row sum += the two (rounded) probabilities of the pair ending at element j."""
+    nt, e = j >> 4, j & 15
+    if ROWSUM == "dot2":
+        acc = V(LACC + 2 * nt + ((e >> 1) & 1))
+        E.e(f"v_dot2_f32_bf16 {acc}, {V(p_word(p_cur, j))}, s{S_ONES}, {acc}")
+    elif ROWSUM == "add":
+        E.e(f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(PX[(j - 1) & 3])}")
+        E.e(f"v_add_f32 {V(LACC + 2 * nt + 1)}, {V(LACC + 2 * nt + 1)}, {V(PX[j & 3])}")
 
 
 def emit_step(E, R, par):
@@ -261,52 +306,57 @@ def emit_step(E, R, par):
         f, nt = i >> 1, i & 1
         if R == 1 and i == 0:                             # V(q) visible; slot of V(q-1) free -> V(q+1)
             E.e("s_waitcnt vmcnt(8)")
-            E.e("s_barrier")
-            emit_issue_page(E, 1, VRING + (1 - par) * PAGE, advance=True)
+            if not ABL & 8:
+                E.e("s_barrier")
+            emit_page_address(E, 1, advance=True)
         if R == 2 and i == 24:                            # K(q+1) visible; slot of K(q) free -> K(q+2)
             E.e("s_waitcnt vmcnt(8)")
-            E.e("s_barrier")
-            emit_issue_page(E, 0, par * PAGE, advance=True)
-        if nt == 0:
+            if not ABL & 8:
+                E.e("s_barrier")
+            emit_page_address(E, 0, advance=True)
+        if nt == 0 and not ABL & 2:
             E.e(f"s_waitcnt lgkmcnt({D_AHEAD - 1})")      # fragment f has landed
         if f < 8:
             E.e(mfma_qk(f == 0, s_next, nt, f, f))
         else:
             g = f - 8
-            E.e(mfma_pv(g >> 1, nt, f, p_prev, g & 1))
-        # fillers: operand prefetch, softmax of s_cur, running max of s_next
-        if nt == 0:
+            E.e(mfma_pv(g & 3, nt, f, p_prev, g >> 2))
+        # fillers: page load, operand prefetch, softmax of s_cur, running max of s_next
+        if R == 1 and i < 8:
+            emit_page_load(E, i, VRING + (1 - par) * PAGE)
+        if R == 2 and i >= 24:
+            emit_page_load(E, i - 24, par * PAGE)
+        if nt == 0 and not ABL & 2:
             fa = f + D_AHEAD
             if fa < 16:
                 E.e(ds_read_frag(fa, frag_source(R, par, fa)))
             else:
                 E.e(ds_read_frag(fa - 16, frag_source(nR, npar, fa - 16)))
-        ent, ee = i >> 4, i & 15
-        E.e(f"v_fma_f32 {V(T_FMA[i & 1])}, {V(s_cur + 16 * ent + ee)}, s{S_C}, {V(NEGM + ent)}")
+        if ABL & 1:
+            continue
         # A trans result is consumed two slots later: on gfx950 a VALU op that reads a v_exp
         # result only a couple of issue slots after it saw stale data in half of the lanes.
-        if i >= 2:
-            emit_finish_element(E, i - 2, p_cur)
-        E.e(f"v_exp_f32 {V(PX[i & 3])}, {V(T_FMA[i & 1])}")
-        for op in max_at.get(i, []):
-            E.e(op)
-    E.e("s_nop 3")
-    emit_finish_element(E, 30, p_cur)
-    emit_finish_element(E, 31, p_cur)
+        if i >= 3 and i % 2 == 1 and not os.environ.get("CA_NOPACK"):
+            emit_pack(E, i - 2, p_cur)
+        if i >= 4 and i % 2 == 0:
+            emit_rowsum(E, i - 3, p_cur)
+        if not os.environ.get("CA_NOEXP"):
+            E.e(f"v_exp_f32 {V(PX[i & 3])}, {V(s_cur + 16 * (i >> 4) + (i & 15))}")
+        if not os.environ.get("CA_NOMAX"):
+            for op in max_at.get(i, []):
+                E.e(op)
+    if ABL & 1:
+        return
+    E.e("s_nop 7")
+    emit_pack(E, 31, p_cur)
+    emit_rowsum(E, 29, p_cur)
+    emit_rowsum(E, 31, p_cur)
     # the tile just produced is exponentiated in the next step: mask its ragged tail, settle m_ref
     if R < 3:
         emit_mask_check(E, s_next, S_PGCUR, R + 1)
     else:
         emit_mask_check(E, s_next, S_PGNEXT, 0)
     emit_settle(E, s_next, p_cur)
-
-
-def emit_finish_element(E, j, p_cur):
-    nt, e = j >> 4, j & 15
-    E.e(f"v_add_f32 {V(LACC + 2 * nt + (e & 1))}, {V(LACC + 2 * nt + (e & 1))}, {V(PX[j & 3])}")
-    if e & 1:
-        dst = V(p_cur + 4 * (2 * nt + (e >> 3)) + ((e & 7) >> 1))
-        E.e(f"v_cvt_pk_bf16_f32 {dst}, {V(PX[(j - 1) & 3])}, {V(PX[j & 3])}")
 
 
 def emit_page_end(E):
@@ -320,12 +370,12 @@ def emit_page_end(E):
 def emit_drain(E, par_last):
     """PV of the final step: V page (parity par_last), keys 96..127, P tile B."""
     for g in range(8):
-        mt, kk = g >> 1, g & 1
+        mt, kk = g & 3, g >> 2
         E.e(f"ds_read_b128 {V(FR + 4 * g, 4)}, {V(XOV + 6 + kk)} offset:{par_last * PAGE + mt * 8192}")
     E.e("s_waitcnt lgkmcnt(0)")
     for g in range(8):
         for nt in range(2):
-            E.e(mfma_pv(g >> 1, nt, g, P_TILE["B"], g & 1))
+            E.e(mfma_pv(g & 3, nt, g, P_TILE["B"], g >> 2))
 
 
 def generate():
@@ -346,7 +396,9 @@ def generate():
         E.e(f"s_sub_i32 s{S_VLAST + sub}, s{S_LASTV}, {32 * sub}")
         E.e(f"s_max_i32 s{S_VLAST + sub}, s{S_VLAST + sub}, 0")
         E.e(f"s_min_i32 s{S_VLAST + sub}, s{S_VLAST + sub}, 32")
-    E.e(f"v_mov_b32 {V(VDMA)}, %[lane_off]")
+    E.e(f"s_mov_b32 s{S_ONES}, 0x3f803f80")
+    for i in range(8):
+        E.e(f"v_add_u32 {V(DMAOFF + i)}, {4096 * i}, %[lane_off]")
     E.e(f"v_mov_b32 {V(TBLLO)}, %[tbl_lo]")
     E.e(f"v_mov_b32 {V(TBLHI)}, %[tbl_hi]")
     E.e(f"v_mov_b32 {V(KIDX)}, %[kidx]")
@@ -359,9 +411,9 @@ def generate():
         E.e(f"v_accvgpr_write_b32 {A(r)}, 0")
     for r in range(4):
         E.e(f"v_mov_b32 {V(LACC + r)}, 0")
-    for nt in range(2):
-        E.e(f"v_mov_b32 {V(NEGM + nt)}, 0x7f800000")      # -m_ref = +inf
-        E.e(f"v_mov_b32 {V(THR + nt)}, 0xff800000")       # m_ref + slack = -inf
+    for nt in range(2):                                   # m_ref = 0 until tile 0 has been seen
+        for i in range(16):
+            E.e(f"v_mov_b32 {V(NT[nt] + i)}, 0")
     for r in range(16):
         E.e(f"v_mov_b32 {V(P_TILE['B'] + r)}, 0")
     E.e(f"s_mov_b32 s{S_PGCUR}, 0")
@@ -386,7 +438,7 @@ def generate():
     for op in tile_max_ops(S_TILE["A"]):
         E.e(op)
     emit_mask_check(E, S_TILE["A"], S_PGCUR, 0)
-    emit_settle(E, S_TILE["A"], P_TILE["B"])
+    emit_settle(E, S_TILE["A"], P_TILE["B"], first=True)
     # first operand fragments of step (R=0, parity 0)
     for f in range(D_AHEAD):
         E.e(ds_read_frag(f, frag_source(0, 0, f)))
@@ -431,7 +483,7 @@ def main(out_path):
         for t in text:
             f.write('"' + t.replace("\\", "\\\\").replace('"', '\\"') + '\\n"\n')
     # registers the block uses beyond its operands (v148..v151 are outputs)
-    clob = [f"v{i}" for i in range(0, 200) if not 144 <= i <= 151 or i in (146, 147)] + [f"s{i}" for i in range(36, 96)]
+    clob = [f"v{i}" for i in range(0, 224) if not 148 <= i <= 151] + [f"s{i}" for i in range(36, 96)]
     clob_path = out_path.replace("attn_core_gfx950.inc", "attn_core_clobbers.inc")
     with open(clob_path, "w") as f:
         f.write("// Generated by gen_attn_core.py -- do not edit.\n#define CA_CORE_CLOBBERS \\\n")
