@@ -251,3 +251,105 @@ def test_c3_wan1p3b_cascade_both_modes_sampled():
 
 def test_c4_wan14b_cascade_sampled():
     _full_shape("c4_wan14b_cascade5", [BI], heads_sample=(0, 1, 17, 39), n_random=8)
+
+
+# --------------------------------------------------------------------------- long rollout (ring buffer)
+
+def test_c5_rollout_ring_buffer():
+    """40 cascade steps at the Wan-1.3B shape: 1 sink + 6-block window + 5 in flight, evict and
+    append every step, prompt switch (re-tag) at step 20.  Slot of every append, snapshot,
+    visibility and page indices are compared bit-exact with the oracle at every step; outputs are
+    compared numerically on sampled rows at steps that cover ramp-up, the first full cascade,
+    the first wrapped ring, the switch and the end."""
+    import torch
+    from paper_2511_20426_amd.runner import CascadePool
+    from paper_2511_20426_amd import binding as B
+    w = W.CONFIGS["c5_wan1p3b_rollout"]
+    L, H, D, C = w.block_tokens, w.heads, w.head_dim, w.max_inflight
+    pool = CascadePool.for_workload(w)
+    cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, C, w.pages_per_block, H)
+    checked = (0, 3, 4, 11, 20, 39)
+    heads_sample = (0, 7, 11)
+    # which (step, position) draws the oracle will need: in-flight data of checked steps, and the
+    # last write (the tc step, position 0) of every block that is cached at a checked step
+    need = set()
+    sim = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, C, w.pages_per_block, H)
+    for step in range(40):
+        b, batch, _ = orc.rollout_step(sim, step, W.TIMESTEPS, 0)
+        if step in checked:
+            need.update((step, i) for i in range(len(batch)))
+            order, states, _ = sim.kv_order([g for g, _ in batch])
+            need.update((g + 4, 0) for g, st in zip(order, states) if st != orc.NOISY)
+        orc.rollout_finish(sim, b, batch)
+    host = {}
+    final_kv = {}                                       # block -> (K, V) written at its tc step
+    gen = torch.Generator(device="cuda:0")
+    epoch = 0
+    t_start = time.time()
+    for step in range(40):
+        if step == 20:
+            epoch = 1
+            before = pool.pool[:1 << 20].clone()
+            cache.retag(epoch)
+            pool.ctx.kv_cache_retag(epoch)
+            assert [s.astuple() for s in pool.ctx.kv_cache_snapshot()] == cache.snapshot()
+            assert torch.equal(before, pool.pool[:1 << 20])          # no K/V byte moves at a prompt switch
+        b, batch = orc.cascade_schedule(step, W.TIMESTEPS, C)
+        infl = [g for g, _ in batch]
+        q_parts = []
+        for i, (g, t) in enumerate(batch):
+            if (step, i) in need:
+                q, k, v = W.draw_step_block(w, step, i)
+                host[(step, i)] = (q, k, v)
+                qt, kt, vt = (Hn.to_torch(x, w.dtype) for x in (q, k, v))
+            else:                                       # never compared: drawn on the device
+                gen.manual_seed(1000 * step + i)
+                qt, kt, vt = ((torch.randn((L, H, D), generator=gen, device="cuda:0") * w.input_scale)
+                              .to(torch.bfloat16) for _ in range(3))
+            slot = pool.append(g, t, epoch, kt, vt)
+            assert slot == cache.append(g, t, epoch)
+            q_parts.append(qt)
+            if t == 0 and (step, i) in host:
+                final_kv[g] = host[(step, i)][1:]
+        assert [s.astuple() for s in pool.ctx.kv_cache_snapshot()] == cache.snapshot()
+        order, states, slots = cache.kv_order(infl)
+        for mode in (BI, CA):
+            vis, kv_ids = pool.ctx.debug_visibility(infl, mode)
+            assert kv_ids == order
+            np.testing.assert_array_equal(np.array(vis, np.uint8), orc.visibility(states, order, infl, mode))
+        for g, s in zip(order, slots):
+            assert pool.ctx.kv_cache_page_index(g, w.pages_per_block - 1, H - 1) == \
+                cache.page_index(s, w.pages_per_block - 1, H - 1)
+        qcat = torch.cat(q_parts)
+        qr = pool.rope(qcat, w.frames_per_block * infl[0])
+        mode = BI if step != 11 else CA                 # one block-causal step on a wrapped ring
+        out = pool.forward(qr, infl, mode)
+        if step in checked:
+            torch.cuda.synchronize()
+            got = Hn.from_torch(out, w.dtype)
+            pos = lambda g: orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w)
+            hs = list(heads_sample)
+            kb, vb = [], []
+            for g, st in zip(order, states):
+                if st == orc.NOISY:
+                    k, v = host[(step, infl.index(g))][1:]
+                else:
+                    k, v = final_kv[g]
+                kb.append(orc.rope3d(W.to_f64(k[:, hs]), pos(g), w.rope_dims, w.rope_theta))
+                vb.append(W.to_f64(v[:, hs]))
+            rows = [W.sample_rows(L, 6, seed=step * 10 + i, tile_edges=(2304,)) for i in range(len(infl))]
+            qb = [orc.rope3d(W.to_f64(host[(step, i)][0][:, hs]), pos(g), w.rope_dims, w.rope_theta)[rows[i]]
+                  for i, g in enumerate(infl)]
+            ref = orc.cascade_attention(qb, kb, vb, orc.visibility(states, order, infl, mode))
+            gsel = [got[i * L:(i + 1) * L][rows[i]][:, hs] for i in range(len(infl))]
+            Hn.assert_close(np.concatenate(gsel), np.concatenate(ref), "bf16", f"rollout step {step}")
+            _say(f"rollout step {step}: {len(infl)} in flight, {len(order)} KV blocks, t={time.time() - t_start:.1f}s")
+        if batch[0][1] == 0:
+            pool.ctx.kv_cache_promote(b)
+            cache.promote(b)
+            win = cache.clean_window()
+            if len(win) > w.window_blocks:
+                pool.ctx.kv_cache_evict(win[0])
+                cache.evict(win[0])
+        assert [s.astuple() for s in pool.ctx.kv_cache_snapshot()] == cache.snapshot()
+    torch.cuda.synchronize()

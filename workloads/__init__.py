@@ -155,6 +155,20 @@ def draw_config(w: Workload, seed: int | None = None, scale: float | None = None
     return draw_qkv(w, w.n_inflight, w.n_cached + w.n_inflight, seed, scale)
 
 
+def draw_step_block(w: Workload, step: int, i: int, seed: int | None = None):
+    """Long-rollout recipe: (Q, K, V) [L,H,D] of the i-th in-flight block of cascade step `step`,
+    each from its own generator seeded by (seed + step, i, tensor) so that any block of any step
+    can be drawn without the others."""
+    base = (w.seed if seed is None else seed) + step
+    out = []
+    for which in range(3):
+        rng = np.random.default_rng([base, i, which])
+        x = rng.standard_normal((w.block_tokens, w.heads, w.head_dim), dtype=np.float32)
+        x *= np.float32(w.input_scale)
+        out.append(store(x, w.dtype))
+    return tuple(out)
+
+
 def split_blocks(x: np.ndarray, L: int) -> List[np.ndarray]:
     assert x.shape[0] % L == 0
     return [x[i * L:(i + 1) * L] for i in range(x.shape[0] // L)]
