@@ -23,6 +23,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6        # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
+# HBM bytes per attention launch at the Wan-14B shape, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# scaled by a 1 GiB copy (profiles/c4_wan14b_cascade5_hbm_traffic.txt): 4294.4 MB read + 240.2 MB written
+ATTN_TRAFFIC_BYTES_C4 = 4.5346e9
 
 
 def cpu_baseline(w, seconds_target=15.0):
@@ -77,6 +80,9 @@ def main() -> int:
     ap.add_argument("--mode", default="bidirectional", choices=["bidirectional", "block_causal"])
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 1 GiB device copy instead (known traffic, for scaling rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (--gpus must be 1)",
@@ -91,6 +97,14 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         return 2
+    if args.copy_calibration:
+        x = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")      # 1 GiB read + 1 GiB written
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": x.numel() * 2, "copy_bytes_written": x.numel() * 2}))
+        return 0
     w = W.CONFIGS[args.workload]
     mode = B.CA_BIDIRECTIONAL if args.mode == "bidirectional" else B.CA_BLOCK_CAUSAL
     dev = torch.device("cuda:0")
@@ -164,7 +178,9 @@ def main() -> int:
                    "step": "5x kv_cache_append + rope3d_apply(Q) + cascade_attn_forward + promote/evict"},
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
-                     "avg_launch_ms": attn_ms, "traffic": None},
+                     "avg_launch_ms": attn_ms,
+                     "traffic": ATTN_TRAFFIC_BYTES_C4 if (w.name == "c4_wan14b_cascade5" and
+                                                          mode == B.CA_BIDIRECTIONAL) else None},
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
