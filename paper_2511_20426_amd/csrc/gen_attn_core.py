@@ -26,7 +26,7 @@ Register map (fixed):
   v[64:79]    P^T tile A, (nt, kk) at v[64 + 4*(2*nt+kk) ..]      v[80:95]  P^T tile B
   v[96:127]   ring of 8 operand fragments
   v[128:135]  LDS address of chunk pair j in the K ring, v[136:143] the same in the V ring
-  v148..v151  row-sum accumulators (nt, parity of the packed pair)
+  v148..v151  row-sum accumulators (column tile, parity of the element)
   v[184:199], v[200:215]  -m_ref of column tile 0 / 1, replicated 16 times: the C operand of the
               first MFMA of every S tile, so a tile comes out of the matrix pipe as s*c - m_ref
   v152..v175  temporaries
@@ -73,7 +73,7 @@ TBLLO, TBLHI, KIDX, XLANE = 177, 178, 179, 180
 DMAOFF = 216         # 216..223: lane's byte offset in a page for load i (+4096 i)
 
 # scalar registers (all inside the clobbered range s36..s95)
-S_C, S_NLEFT, S_P, S_PM1, S_STRIDE, S_NKVB = 40, 41, 42, 43, 44, 45
+S_NLEFT, S_P, S_PM1, S_STRIDE, S_NKVB = 41, 42, 43, 44, 45
 S_POOL = 46          # 46,47
 S_M0B, S_LASTV = 48, 49
 S_VLAST = 50         # 50..53
@@ -83,7 +83,6 @@ S_T = 60             # 60..69 temporaries
 S_ADDR = 70          # 70,71
 S_VCC = 72           # 72,73
 S_LDS0 = 74
-S_ONES = 75          # bf16 pair (1.0, 1.0)
 
 
 class Emitter:
@@ -277,18 +276,13 @@ def emit_pack(E, j, p_cur):
     E.e(f"v_cvt_pk_bf16_f32 {V(p_word(p_cur, j))}, {V(PX[(j - 1) & 3])}, {V(PX[j & 3])}")
 
 
-ROWSUM = os.environ.get("CA_ROWSUM", "add")     # v_dot2_f32_bf16 on the packed pair measured 2.3 ms slower per forward
-
-
 def emit_rowsum(E, j, p_cur):
-    """row sum += the two (rounded) probabilities of the pair ending at element j."""
-    nt, e = j >> 4, j & 15
-    if ROWSUM == "dot2":
-        acc = V(LACC + 2 * nt + ((e >> 1) & 1))
-        E.e(f"v_dot2_f32_bf16 {acc}, {V(p_word(p_cur, j))}, s{S_ONES}, {acc}")
-    elif ROWSUM == "add":
-        E.e(f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(PX[(j - 1) & 3])}")
-        E.e(f"v_add_f32 {V(LACC + 2 * nt + 1)}, {V(LACC + 2 * nt + 1)}, {V(PX[j & 3])}")
+    """row sums += the two (unrounded) probabilities of the pair ending at element j: one
+    accumulator for even, one for odd elements of each column tile.  (A v_dot2_f32_bf16 on the packed
+    pair would halve the instruction count but measured 2.3 ms slower per forward.)"""
+    nt = j >> 4
+    E.e(f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(PX[(j - 1) & 3])}")
+    E.e(f"v_add_f32 {V(LACC + 2 * nt + 1)}, {V(LACC + 2 * nt + 1)}, {V(PX[j & 3])}")
 
 
 def emit_step(E, R, par):
@@ -336,15 +330,13 @@ def emit_step(E, R, par):
             continue
         # A trans result is consumed two slots later: on gfx950 a VALU op that reads a v_exp
         # result only a couple of issue slots after it saw stale data in half of the lanes.
-        if i >= 3 and i % 2 == 1 and not os.environ.get("CA_NOPACK"):
+        if i >= 3 and i % 2 == 1:
             emit_pack(E, i - 2, p_cur)
         if i >= 4 and i % 2 == 0:
             emit_rowsum(E, i - 3, p_cur)
-        if not os.environ.get("CA_NOEXP"):
-            E.e(f"v_exp_f32 {V(PX[i & 3])}, {V(s_cur + 16 * (i >> 4) + (i & 15))}")
-        if not os.environ.get("CA_NOMAX"):
-            for op in max_at.get(i, []):
-                E.e(op)
+        E.e(f"v_exp_f32 {V(PX[i & 3])}, {V(s_cur + 16 * (i >> 4) + (i & 15))}")
+        for op in max_at.get(i, []):
+            E.e(op)
     if ABL & 1:
         return
     E.e("s_nop 7")
@@ -381,7 +373,6 @@ def emit_drain(E, par_last):
 def generate():
     E = Emitter()
     # ---- set-up: inputs to fixed registers
-    E.e(f"s_mov_b32 s{S_C}, %[c]")
     E.e(f"s_mov_b32 s{S_NLEFT}, %[n_pages]")
     E.e(f"s_mov_b32 s{S_P}, %[ppb]")
     E.e(f"s_sub_u32 s{S_PM1}, s{S_P}, 1")
@@ -396,7 +387,6 @@ def generate():
         E.e(f"s_sub_i32 s{S_VLAST + sub}, s{S_LASTV}, {32 * sub}")
         E.e(f"s_max_i32 s{S_VLAST + sub}, s{S_VLAST + sub}, 0")
         E.e(f"s_min_i32 s{S_VLAST + sub}, s{S_VLAST + sub}, 32")
-    E.e(f"s_mov_b32 s{S_ONES}, 0x3f803f80")
     for i in range(8):
         E.e(f"v_add_u32 {V(DMAOFF + i)}, {4096 * i}, %[lane_off]")
     E.e(f"v_mov_b32 {V(TBLLO)}, %[tbl_lo]")

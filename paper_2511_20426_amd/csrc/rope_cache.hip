@@ -40,13 +40,24 @@ __device__ __forceinline__ TokenPos token_pos(int64_t n, int64_t first_frame, in
   return p;
 }
 
-// cos/sin of pair `pair` at a token position; fp64 trig, fp32 result.
+// cos/sin of pair `pair` at a token position.  The angle pos * freq is formed and reduced to
+// [-pi, pi] in fp64 (exact to ~1e-15 for any position).  FP64_TRIG evaluates sin/cos in fp64 (fp32
+// storage: results correctly rounded to fp32); otherwise in fp32 on the reduced angle, whose error
+// (~1e-7) is far below the bf16 rounding (4e-3) of what it multiplies, at a fraction of the cost.
+template <bool FP64_TRIG>
 __device__ __forceinline__ void pair_cs(const RopeGeom& g, const TokenPos& p, int pair, float* c, float* s) {
   const int pos = pair < g.pairs_t ? p.f : (pair < g.pairs_t + g.pairs_h ? p.y : p.x);
-  double sd, cd;
-  sincos(double(pos) * g.freq[pair], &sd, &cd);
-  *c = float(cd);
-  *s = float(sd);
+  const double ang = double(pos) * g.freq[pair];
+  if (FP64_TRIG) {
+    double sd, cd;
+    sincos(ang, &sd, &cd);
+    *c = float(cd);
+    *s = float(sd);
+  } else {
+    const double turns = rint(ang * 0.15915494309189535);                 // nearest multiple of 2 pi
+    const float r = float(fma(turns, -6.283185307179586, ang));
+    sincosf(r, s, c);
+  }
 }
 
 // ----------------------------------------------------------------------------- generic path
@@ -111,7 +122,7 @@ __global__ __launch_bounds__(256) void rope_generic_kernel(RopeGeom g, GenericAr
   const TokenPos p = token_pos(pad ? 0 : n, a.first_frame, g.grid_h, g.grid_w);
   float cs[4], sn[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) pair_cs(g, p, c8 * 4 + j, &cs[j], &sn[j]);
+  for (int j = 0; j < 4; ++j) pair_cs<sizeof(T) == 4>(g, p, c8 * 4 + j, &cs[j], &sn[j]);
   const int h0 = blockIdx.y * a.heads_per_group;
   const int h1 = min(h0 + a.heads_per_group, g.heads);
   const T* x = static_cast<const T*>(a.x);
@@ -169,7 +180,7 @@ __global__ __launch_bounds__(256) void cache_write_bf16_kernel(RopeGeom g, Paged
     const int n = tok0 + r0 + 16 * i;
     const TokenPos p = token_pos(min(n, a.block_tokens - 1), a.first_frame, g.grid_h, g.grid_w);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) pair_cs(g, p, c * 4 + j, &cs[i][j], &sn[i][j]);
+    for (int j = 0; j < 4; ++j) pair_cs<false>(g, p, c * 4 + j, &cs[i][j], &sn[i][j]);
   }
 
   const int h0 = blockIdx.y * a.heads_per_group;
