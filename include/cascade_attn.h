@@ -41,6 +41,8 @@
  *          16*(c/2) + perm[8*(c%2) + e], perm = {0,1,2,3,8,9,10,11,4,5,6,7,12,13,14,15}
  *          (the order in which an MFMA 32x32 accumulator hands P to the next MFMA).
  *   Rows/tokens past the end of a block's last page are stored as zeros.
+ * For bf16 the pool ends with a fixed scratch area (about 35 MB) that cascade_attn_forward uses
+ * for partial results; forwards on one context must therefore not overlap on the GPU.
  */
 #ifndef CASCADE_ATTN_H
 #define CASCADE_ATTN_H
@@ -150,8 +152,8 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
                             int32_t n_inflight, int32_t mode, uint8_t* vis,
                             int64_t* kv_block_ids, int32_t cap, int32_t* n_kv_out);
 
-/* Selects an attention kernel variant for experiments (0 = default).  Unknown values are
- * rejected with CA_EINVAL. */
+/* Selects an attention kernel variant for experiments: 0 = default, 1 = no tail balancing (every
+ * workgroup walks its whole KV range).  Unknown values are rejected with CA_EINVAL. */
 int32_t ca_set_kernel_variant(ca_ctx* ctx, int32_t variant);
 
 const char* ca_strerror(int32_t code);

@@ -55,8 +55,35 @@ struct AttnArgs {
   int32_t seg_row0[kMaxSeg], seg_rows[kMaxSeg], seg_nvis[kMaxSeg], seg_tile0[kMaxSeg + 1];
   int32_t kv_slot[kMaxKvBlocks];
   int32_t tiles_per_head, total_work, work_per_xcd;
+  // Tail balancing: the last `split_items` work items of every XCD's range have their KV walk cut
+  // into `split` page ranges, one workgroup each, so that the launch's last, partly filled round
+  // of workgroups is shorter; their partial results meet in merge_partials_kernel.
+  int32_t split, split_items, full_items;   // per XCD: full_items + split_items == work_per_xcd
+  float* partials;                     // [xcd][split item][chunk][kPartialFloats]
   float c;                             // log2(e) / sqrt(head_dim)
 };
+
+// one partial result of a 256-row tile: O^T contributions [row][128] (fp32, not normalised),
+// then the row's exponent reference (log2 units) and row sum
+constexpr int kPartialRow = 132;                 // floats per row: 128 + reference + sum, padded to 16 B
+constexpr int kPartialFloats = kRowsPerWg * kPartialRow;
+static_assert(size_t(kMaxPartials) * kPartialFloats * 4 == kAttnScratchBytes, "scratch size");
+
+struct WorkItem {
+  int h, row0, rows_end, n_kvb;
+};
+
+__device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int work) {
+  WorkItem w;
+  w.h = work / a.tiles_per_head;
+  const int tile = work - w.h * a.tiles_per_head;
+  int seg = 0;
+  while (seg + 1 < a.n_seg && tile >= a.seg_tile0[seg + 1]) ++seg;
+  w.row0 = a.seg_row0[seg] + (tile - a.seg_tile0[seg]) * kRowsPerWg;
+  w.rows_end = a.seg_row0[seg] + a.seg_rows[seg];
+  w.n_kvb = a.seg_nvis[seg];
+  return w;
+}
 
 __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
   f32x2 f = {lo, hi};
@@ -78,18 +105,24 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, hi = lane >> 5, sw = lane & 15;
 
-  // ---- which (head, row tile): XCD x takes work items [x*work_per_xcd, (x+1)*work_per_xcd)
+  // ---- which (head, row tile, page range): XCD x takes work items [x*work_per_xcd, (x+1)*work_per_xcd);
+  // inside an XCD the full items come first, then `split` workgroups per split item
   const int xcd = blockIdx.x & 7, nth = blockIdx.x >> 3;
-  const int work = xcd * a.work_per_xcd + nth;
-  if (nth >= a.work_per_xcd || work >= a.total_work) return;
-  const int h = work / a.tiles_per_head;
-  const int tile = work - h * a.tiles_per_head;
-  int seg = 0;
-  while (seg + 1 < a.n_seg && tile >= a.seg_tile0[seg + 1]) ++seg;
-  const int row0 = a.seg_row0[seg] + (tile - a.seg_tile0[seg]) * kRowsPerWg;
-  const int rows_end = a.seg_row0[seg] + a.seg_rows[seg];
-  const int n_kvb = a.seg_nvis[seg];
-  const int n_pages = n_kvb * a.pages_per_block;
+  int item = nth, chunk = 0, n_chunks = 1;
+  if (nth >= a.full_items) {
+    item = a.full_items + (nth - a.full_items) / a.split;
+    chunk = (nth - a.full_items) % a.split;
+    n_chunks = a.split;
+  }
+  const int work = xcd * a.work_per_xcd + item;
+  if (item >= a.work_per_xcd || work >= a.total_work) return;
+  const WorkItem wi = decode_item(a, work);
+  const int h = wi.h, row0 = wi.row0, rows_end = wi.rows_end, n_kvb = wi.n_kvb;
+  const int all_pages = n_kvb * a.pages_per_block;
+  const int page_lo = int(int64_t(all_pages) * chunk / n_chunks);
+  const int page_hi = int(int64_t(all_pages) * (chunk + 1) / n_chunks);
+  const int n_pages = page_hi - page_lo;
+  const int kb0 = page_lo / a.pages_per_block, pg0 = page_lo - kb0 * a.pages_per_block;
 
   // ---- Q fragments: B operand of S^T = K Q^T.  Lane holds dims 16ks + 8hi .. +7 of query l31
   // of column tile nt; fragment (nt, ks) goes to a[128 + 4*(8nt + ks) ..].
@@ -132,22 +165,45 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     *reinterpret_cast<u32x4*>(lds + kVRing + kPageBytes + (i * 256 + tid) * 16) = u32x4{0, 0, 0, 0};
 
   f32x16 o0, o1, o2, o3, o4, o5, o6, o7;
-  float l0a, l0b, l1a, l1b;
+  float l0a, l0b, l1a, l1b, negm0, negm1;
   asm volatile(
 #include "attn_core_gfx950.inc"
-      : "={a[0:15]}"(o0), "={a[16:31]}"(o1), "={a[32:47]}"(o2), "={a[48:63]}"(o3), "={a[64:79]}"(o4),
-        "={a[80:95]}"(o5), "={a[96:111]}"(o6), "={a[112:127]}"(o7), "=&{v148}"(l0a), "=&{v149}"(l0b),
-        "=&{v150}"(l1a), "=&{v151}"(l1b)
+      : "=&{v[0:15]}"(o0), "=&{v[16:31]}"(o1), "=&{v[32:47]}"(o2), "=&{v[48:63]}"(o3), "=&{v[64:79]}"(o4),
+        "=&{v[80:95]}"(o5), "=&{v[96:111]}"(o6), "=&{v[112:127]}"(o7), "=&{v148}"(l0a), "=&{v149}"(l0b),
+        "=&{v150}"(l1a), "=&{v151}"(l1b), "=&{v184}"(negm0), "=&{v200}"(negm1)
       : "{a[128:143]}"(qt[0]), "{a[144:159]}"(qt[1]), "{a[160:175]}"(qt[2]), "{a[176:191]}"(qt[3]),
         [xo0] "v"(xo0), [lane_off] "v"(lane_off), [tbl_lo] "v"(tbl_lo), [tbl_hi] "v"(tbl_hi),
-        [kidx] "v"(kidx), [xlane] "v"(xlane), [pool] "s"(a.pool), [n_pages] "s"(n_pages), [n_kvb] "s"(n_kvb),
+        [kidx] "v"(kidx), [xlane] "v"(xlane), [pool] "s"(a.pool), [n_pages] "s"(n_pages), [n_kvb] "s"(n_kvb), [kb0] "s"(kb0), [pg0] "s"(pg0),
         [ppb] "s"(a.pages_per_block), [stride] "s"(stride), [last_valid] "s"(a.last_valid),
         [wave] "s"(wave_s), [lds0] "s"(lds0)
       : "memory", "vcc", "scc", "m0", CA_CORE_CLOBBERS);
 
   // ---- normalise and store: lane holds, for its query, dims 32mt + 8(i/4) + 4hi + (i%4)
-  const f32x16* oacc[4][2] = {{&o0, &o1}, {&o2, &o3}, {&o4, &o5}, {&o6, &o7}};
+  const f32x16 oacc[4][2] = {{o0, o1}, {o2, o3}, {o4, o5}, {o6, o7}};
   const float l_lane[2] = {l0a + l0b, l1a + l1b};
+  if (n_chunks > 1) {
+    // partial result: accumulators as they are, plus (m_ref, row sum) per row
+    float* part = a.partials + (size_t(xcd * a.split_items + (item - a.full_items)) * a.split + chunk) * kPartialFloats;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      const float l_tot = l_lane[nt] + other_half(l_lane[nt]);
+      const int r = wave * 64 + nt * 32 + l31;
+      float* rp = part + r * kPartialRow;
+#pragma unroll
+      for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x16& o = oacc[mt][nt];
+          const float x0 = o[4 * g + 0], x1 = o[4 * g + 1], x2 = o[4 * g + 2], x3 = o[4 * g + 3];
+          *reinterpret_cast<float4*>(rp + 32 * mt + 8 * g + 4 * hi) = make_float4(x0, x1, x2, x3);
+        }
+      if (hi == 0) {
+        rp[128] = -(nt ? negm1 : negm0);
+        rp[129] = l_tot;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
     const float l_tot = l_lane[nt] + other_half(l_lane[nt]);
@@ -158,7 +214,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
       for (int mt = 0; mt < 4; ++mt)
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const f32x16& o = *oacc[mt][nt];
+          const f32x16& o = oacc[mt][nt];
           u32x2 w;
           w[0] = pack2(o[4 * g + 0] * inv, o[4 * g + 1] * inv);
           w[1] = pack2(o[4 * g + 2] * inv, o[4 * g + 3] * inv);
@@ -168,12 +224,48 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
   }
 }
 
+
+// Combines the partial results of the split work items: for every row, the partials are brought
+// to the largest of their exponent references, summed and normalised.
+__global__ __launch_bounds__(256) void merge_partials_kernel(AttnArgs a) {
+  const int xcd = blockIdx.x / a.split_items, sidx = blockIdx.x % a.split_items;
+  const int work = xcd * a.work_per_xcd + a.full_items + sidx;
+  if (work >= a.total_work) return;
+  const WorkItem wi = decode_item(a, work);
+  const int r = threadIdx.x, row = wi.row0 + r;
+  if (row >= wi.rows_end) return;
+  const float* part = a.partials + size_t(xcd * a.split_items + sidx) * a.split * kPartialFloats + r * kPartialRow;
+  float m = -INFINITY;
+  for (int c = 0; c < a.split; ++c) m = fmaxf(m, part[c * kPartialFloats + 128]);
+  float wgt[8], l = 0.f;
+  for (int c = 0; c < a.split; ++c) {
+    wgt[c] = __builtin_amdgcn_exp2f(part[c * kPartialFloats + 128] - m);
+    l += wgt[c] * part[c * kPartialFloats + 129];
+  }
+  const float inv = 1.0f / l;
+  uint16_t* op = a.o + (int64_t(row) * a.heads + wi.h) * 128;
+  for (int d = 0; d < 128; d += 8) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < a.split; ++c) {
+      const float4 x = *reinterpret_cast<const float4*>(part + c * kPartialFloats + d);
+      const float4 y = *reinterpret_cast<const float4*>(part + c * kPartialFloats + d + 4);
+      acc[0] += wgt[c] * x.x; acc[1] += wgt[c] * x.y; acc[2] += wgt[c] * x.z; acc[3] += wgt[c] * x.w;
+      acc[4] += wgt[c] * y.x; acc[5] += wgt[c] * y.y; acc[6] += wgt[c] * y.z; acc[7] += wgt[c] * y.w;
+    }
+    u32x4 w;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w[j] = pack2(acc[2 * j] * inv, acc[2 * j + 1] * inv);
+    *reinterpret_cast<u32x4*>(op + d) = w;
+  }
+}
+
 }  // namespace
 
-int32_t attn_bf16_variant_ok(int variant) { return variant == 0 ? CA_OK : CA_EINVAL; }
+// variant 0: default; 1: no tail balancing (every work item walks its whole KV range)
+int32_t attn_bf16_variant_ok(int variant) { return variant == 0 || variant == 1 ? CA_OK : CA_EINVAL; }
 
 int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
-                         void* stream) {
+                         void* scratch, void* stream) {
   if (p.head_dim != 128 || p.page_tokens != 128) return CA_EUNSUPPORTED;
   if (attn_bf16_variant_ok(variant) != CA_OK) return CA_EINVAL;
   AttnArgs a{};
@@ -212,7 +304,34 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
   a.total_work = tiles * p.heads;
   a.work_per_xcd = (a.total_work + 7) / 8;
   a.c = 1.4426950408889634f / sqrtf(float(p.head_dim));
-  const dim3 grid((unsigned)(a.work_per_xcd * 8));
+  // Tail balancing.  One workgroup occupies a CU, an XCD has n_cu/8 of them, and all items of a
+  // launch take about the same time: after floor(items / cus) full rounds, `rem` items would run
+  // alone while the other CUs idle.  Their KV walks are cut into split = floor(cus / rem) ranges.
+  static int cus_per_xcd = 0;
+  if (cus_per_xcd == 0) {
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return finish_launch("hipDeviceGetAttribute");
+    cus_per_xcd = n_cu >= 8 ? n_cu / 8 : 1;
+  }
+  a.split = 1;
+  a.split_items = 0;
+  a.full_items = a.work_per_xcd;
+  a.partials = static_cast<float*>(scratch);
+  const int rem = a.work_per_xcd % cus_per_xcd;
+  const int min_pages = p.n_vis[0] * p.pages_per_block;        // shortest KV walk of the launch
+  if (scratch && variant == 0 && rem > 0 && a.work_per_xcd > cus_per_xcd) {
+    int split = cus_per_xcd / rem;
+    if (split > 8) split = 8;
+    while (split > 1 && (min_pages < 8 * split || 8 * rem * split > kMaxPartials)) --split;
+    if (split > 1) {
+      a.split = split;
+      a.split_items = rem;
+      a.full_items = a.work_per_xcd - rem;
+    }
+  }
+  const dim3 grid((unsigned)((a.full_items + a.split_items * a.split) * 8));
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel),
@@ -221,6 +340,9 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
     attr_set = true;
   }
   hipLaunchKernelGGL(attn_bf16_kernel, grid, dim3(256), 4 * kPageBytes, static_cast<hipStream_t>(stream), a);
+  if (a.split > 1)
+    hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(8 * a.split_items)), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), a);
   return finish_launch("attn_bf16.hip");
 }
 

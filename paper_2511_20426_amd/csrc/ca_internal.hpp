@@ -13,6 +13,10 @@ namespace ca {
 constexpr int kMaxPairs = 64;      // head_dim <= 128
 constexpr int kMaxKvBlocks = 32;   // sink + window + max_inflight
 constexpr int kMaxInflight = 8;
+// Scratch behind the bf16 pool pages: partial results of the attention kernel's split work items
+// (at most kMaxPartials of them, one 256-row tile of fp32 accumulators + reference + row sum each).
+constexpr int kMaxPartials = 256;
+constexpr size_t kAttnScratchBytes = size_t(kMaxPartials) * 256 * 132 * 4;
 
 // ----------------------------------------------------------------------------- host metadata
 // Slot map, tags and the visibility rule; plain C++, no HIP (Sec. 3.3: shared KV pool with a
@@ -29,7 +33,8 @@ class CacheMeta {
   size_t elem_bytes() const { return cfg_.dtype == CA_BF16 ? 2 : 4; }
   size_t page_elems() const { return size_t(cfg_.page_tokens) * cfg_.head_dim; }
   size_t pair_bytes() const { return 2 * page_elems() * elem_bytes(); }
-  size_t pool_bytes() const { return size_t(n_slots_) * P_ * cfg_.heads * pair_bytes(); }
+  size_t page_bytes_total() const { return size_t(n_slots_) * P_ * cfg_.heads * pair_bytes(); }
+  size_t pool_bytes() const { return page_bytes_total() + (cfg_.dtype == CA_BF16 ? kAttnScratchBytes : 0); }
 
   int32_t slot_of(int64_t g, int32_t* slot) const;       // the fixed rule, resident or not
   int32_t find(int64_t g, int32_t* slot) const;          // CA_ENOENT unless resident
@@ -87,7 +92,7 @@ struct AttnPlan {
 
 int32_t launch_attn_f32(const AttnPlan& p, const void* q, void* out, const void* pool, void* stream);
 int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
-                         void* stream);
+                         void* scratch, void* stream);
 int32_t attn_bf16_variant_ok(int variant);
 
 // Launchers end with this: CA_OK, or CA_EDEVICE after recording the HIP error text.

@@ -406,11 +406,15 @@ def generate():
             E.e(f"v_mov_b32 {V(NT[nt] + i)}, 0")
     for r in range(16):
         E.e(f"v_mov_b32 {V(P_TILE['B'] + r)}, 0")
-    E.e(f"s_mov_b32 s{S_PGCUR}, 0")
-    E.e(f"s_cmp_eq_u32 s{S_P}, 1")
-    E.e(f"s_cselect_b32 s{S_PGNEXT}, 0, 1")
-    for r in (S_KKB, S_KPG, S_VKB, S_VPG):
-        E.e(f"s_mov_b32 s{r}, 0")
+    # the walk starts at page pg0 of visible block kb0 (0, 0 unless the KV range of a tile is split)
+    E.e(f"s_mov_b32 s{S_PGCUR}, %[pg0]")
+    E.e(f"s_add_u32 s{S_T}, s{S_PGCUR}, 1")
+    E.e(f"s_cmp_eq_u32 s{S_T}, s{S_P}")
+    E.e(f"s_cselect_b32 s{S_PGNEXT}, 0, s{S_T}")
+    for r in (S_KKB, S_VKB):
+        E.e(f"s_mov_b32 s{r}, %[kb0]")
+    for r in (S_KPG, S_VPG):
+        E.e(f"s_mov_b32 s{r}, %[pg0]")
     # ---- K(0), V(0), K(1) in flight; wait for the first two, publish
     emit_issue_page(E, 0, 0, advance=False)
     emit_issue_page(E, 1, VRING, advance=False)
@@ -459,6 +463,8 @@ def generate():
     E.e(f"{done}:")
     E.e("s_waitcnt vmcnt(0)")                              # trailing (unused) page loads have landed
     E.e("s_nop 15\ns_nop 15\ns_nop 15")                    # the last MFMAs have written back
+    for r in range(128):                                   # results leave in v[0:127]
+        E.e(f"v_accvgpr_read_b32 {V(r)}, {A(r)}")
     return E.lines
 
 
@@ -473,7 +479,7 @@ def main(out_path):
         for t in text:
             f.write('"' + t.replace("\\", "\\\\").replace('"', '\\"') + '\\n"\n')
     # registers the block uses beyond its operands (v148..v151 are outputs)
-    clob = [f"v{i}" for i in range(0, 224) if not 148 <= i <= 151] + [f"s{i}" for i in range(36, 96)]
+    clob = [f"v{i}" for i in range(128, 224) if not 148 <= i <= 151 and i not in (184, 200)] + [f"a{i}" for i in range(0, 128)] + [f"s{i}" for i in range(36, 96)]
     clob_path = out_path.replace("attn_core_gfx950.inc", "attn_core_clobbers.inc")
     with open(clob_path, "w") as f:
         f.write("// Generated by gen_attn_core.py -- do not edit.\n#define CA_CORE_CLOBBERS \\\n")
