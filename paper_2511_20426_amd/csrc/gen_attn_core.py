@@ -285,15 +285,28 @@ def emit_rowsum(E, j, p_cur):
     E.e(f"v_add_f32 {V(LACC + 2 * nt + 1)}, {V(LACC + 2 * nt + 1)}, {V(PX[j & 3])}")
 
 
+def exp_slot(e):
+    """Issue slot of the exponential of element e (0..31) of the tile: two each in slots 0 and 1,
+    then one per slot, so that the last one issues in slot 29 and everything derived from it
+    (pack, row sum) still fits under the step's last MFMAs."""
+    return e >> 1 if e < 4 else e - 2
+
+
 def emit_step(E, R, par):
     cur, nxt = ("A", "B") if R % 2 == 0 else ("B", "A")
     s_cur, s_next = S_TILE[cur], S_TILE[nxt]
     p_prev, p_cur = (P_TILE["B"], P_TILE["A"]) if R % 2 == 0 else (P_TILE["A"], P_TILE["B"])
     nR, npar = ((R + 1) & 3, par if R < 3 else 1 - par)
     max_ops = tile_max_ops(s_next)
-    max_at = {}                                           # slot -> ops (slots 20..31)
+    max_at = {}                                           # slot -> ops (slots 18..29: QK retired)
     for k, op in enumerate(max_ops):
-        max_at.setdefault(20 + (k * 12) // 16, []).append(op)
+        max_at.setdefault(18 + (k * 12) // 16, []).append(op)
+    exps_at, packs_at = {}, {}
+    for e in range(32):
+        exps_at.setdefault(exp_slot(e), []).append(e)
+        if e & 1:                                         # a trans result is consumed >= 2 slots later
+            packs_at.setdefault(exp_slot(e) + 2, []).append(e)
+    px_holds = {}                                         # PX register -> element, to check the ring
 
     E.e(f"; ---- step R={R} parity={par}")
     for i in range(32):
@@ -328,26 +341,24 @@ def emit_step(E, R, par):
                 E.e(ds_read_frag(fa - 16, frag_source(nR, npar, fa - 16)))
         if ABL & 1:
             continue
-        # A trans result is consumed two slots later: on gfx950 a VALU op that reads a v_exp
-        # result only a couple of issue slots after it saw stale data in half of the lanes.
-        if i >= 3 and i % 2 == 1:
-            emit_pack(E, i - 2, p_cur)
-        if i >= 4 and i % 2 == 0:
-            emit_rowsum(E, i - 3, p_cur)
-        E.e(f"v_exp_f32 {V(PX[i & 3])}, {V(s_cur + 16 * (i >> 4) + (i & 15))}")
+        for j in packs_at.get(i, []):
+            assert px_holds[PX[(j - 1) & 3]] == j - 1 and px_holds[PX[j & 3]] == j
+            emit_pack(E, j, p_cur)
+            emit_rowsum(E, j, p_cur)
+        for e in exps_at.get(i, []):
+            px_holds[PX[e & 3]] = e
+            E.e(f"v_exp_f32 {V(PX[e & 3])}, {V(s_cur + 16 * (e >> 4) + (e & 15))}")
         for op in max_at.get(i, []):
             E.e(op)
+        # the tile just produced is exponentiated in the next step: mask its ragged tail (slot 30),
+        # then settle the exponent reference (after the last MFMA)
+        if i == 30:
+            if R < 3:
+                emit_mask_check(E, s_next, S_PGCUR, R + 1)
+            else:
+                emit_mask_check(E, s_next, S_PGNEXT, 0)
     if ABL & 1:
         return
-    E.e("s_nop 7")
-    emit_pack(E, 31, p_cur)
-    emit_rowsum(E, 29, p_cur)
-    emit_rowsum(E, 31, p_cur)
-    # the tile just produced is exponentiated in the next step: mask its ragged tail, settle m_ref
-    if R < 3:
-        emit_mask_check(E, s_next, S_PGCUR, R + 1)
-    else:
-        emit_mask_check(E, s_next, S_PGNEXT, 0)
     emit_settle(E, s_next, p_cur)
 
 
