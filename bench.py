@@ -24,8 +24,9 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6        # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
 # HBM bytes per attention launch at the Wan-14B shape, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# scaled by a 1 GiB copy (profiles/c4_wan14b_cascade5_hbm_traffic.txt): 4294.4 MB read + 240.2 MB written
-ATTN_TRAFFIC_BYTES_C4 = 4.5346e9
+# scaled by a 1 GiB copy (profiles/c4_wan14b_cascade5_hbm_traffic.txt): 4295.3 MB read + 259.6 MB written
+# by the attention kernel, 26.2 + 8.3 MB by the merge of its split work items
+ATTN_TRAFFIC_BYTES_C4 = 4.5894e9
 
 
 def cpu_baseline(w, seconds_target=15.0):
