@@ -61,7 +61,9 @@ __device__ __forceinline__ void pair_cs(const RopeGeom& g, const TokenPos& p, in
 }
 
 // ----------------------------------------------------------------------------- generic path
-// One thread owns 4 consecutive pairs (8 elements) of one token and walks a range of heads.
+// One thread owns 4 consecutive pairs (8 elements) of one token and walks a range of heads; the 64
+// lanes of a wave cover one token: 64/chunks neighbouring heads x all chunks, i.e. up to 1 KB of
+// contiguous memory per load when heads are adjacent in memory.
 // MODE 0: y[token][head][dim] (rope3d_apply).  MODE 1: K/V pages of the fp32 pool layout
 // (row-major [token][dim] pages), V copied unrotated.
 template <typename T> struct Vec8;
@@ -113,11 +115,13 @@ struct GenericArgs {
 
 template <typename T, int MODE>
 __global__ __launch_bounds__(256) void rope_generic_kernel(RopeGeom g, GenericArgs a) {
-  const int chunks = g.head_dim / 8;
-  const int64_t item = int64_t(blockIdx.x) * 256 + threadIdx.x;
-  if (item >= a.n_tokens * chunks) return;
-  const int64_t n = item / chunks;
-  const int c8 = int(item % chunks);
+  const int chunks = g.head_dim / 8;              // 4, 8 or 16
+  const int head_slots = 64 / chunks;             // heads a wave touches per load
+  const int64_t n = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (n >= a.n_tokens) return;
+  const int lane = threadIdx.x & 63;
+  const int c8 = lane % chunks;
+  const int hs = lane / chunks;
   const bool pad = MODE == 1 && n >= a.valid_tokens;
   const TokenPos p = token_pos(pad ? 0 : n, a.first_frame, g.grid_h, g.grid_w);
   float cs[4], sn[4];
@@ -126,7 +130,7 @@ __global__ __launch_bounds__(256) void rope_generic_kernel(RopeGeom g, GenericAr
   const int h0 = blockIdx.y * a.heads_per_group;
   const int h1 = min(h0 + a.heads_per_group, g.heads);
   const T* x = static_cast<const T*>(a.x);
-  for (int h = h0; h < h1; ++h) {
+  for (int h = h0 + hs; h < h1; h += head_slots) {
     const int64_t src = n * a.tok_stride + int64_t(h) * a.head_stride + c8 * 8;
     Vec8<T> e, w;
 #pragma unroll
@@ -253,8 +257,7 @@ int32_t launch_rope_apply(const RopeGeom& g, int dtype, const void* x, void* y, 
   a.x = x; a.v = nullptr; a.y = y;
   a.n_tokens = n_tokens; a.first_frame = first_frame;
   a.tok_stride = tok_stride; a.head_stride = head_stride;
-  const int64_t items = n_tokens * (g.head_dim / 8);
-  const int64_t gx = (items + 255) / 256;
+  const int64_t gx = (n_tokens + 3) / 4;           // one wave per token, four per workgroup
   if (gx > 0x7fffffff) return CA_EINVAL;
   // enough workgroups to fill 256 CUs several times over, few enough to amortise the trig
   int groups = 1;
@@ -298,8 +301,7 @@ int32_t launch_cache_write(const RopeGeom& g, int dtype, const void* k, const vo
     a.tok_stride = tok_stride; a.head_stride = head_stride;
     a.page_tokens = page_tokens; a.pages_per_block = pages_per_block; a.slot = slot;
     a.heads_per_group = g.heads;
-    const int64_t items = a.n_tokens * (g.head_dim / 8);
-    const dim3 grid((unsigned)((items + 255) / 256), 1);
+    const dim3 grid((unsigned)((a.n_tokens + 3) / 4), 1);
     hipLaunchKernelGGL((rope_generic_kernel<float, 1>), grid, dim3(256), 0, s, g, a);
   }
   return finish_launch("rope_cache.hip");
