@@ -80,6 +80,10 @@ def main() -> int:
     ap.add_argument("--workload", default="c4_wan14b_cascade5")
     ap.add_argument("--mode", default="bidirectional", choices=["bidirectional", "block_causal"])
     ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--inflight", type=int, default=None,
+                    help="blocks in flight (cascade types P1..P4 of Fig. 7: 1, 2, 3, 5); default: the workload's")
+    ap.add_argument("--cached", type=int, default=None,
+                    help="clean cached blocks (2 = the paper's 7-block window accounting); default: the workload's")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead (known traffic, for scaling rocprofv3's "
@@ -107,6 +111,16 @@ def main() -> int:
         print(json.dumps({"copy_bytes_read": x.numel() * 2, "copy_bytes_written": x.numel() * 2}))
         return 0
     w = W.CONFIGS[args.workload]
+    if args.inflight is not None or args.cached is not None:
+        from dataclasses import replace
+        ni = w.n_inflight if args.inflight is None else args.inflight
+        nc = w.n_cached if args.cached is None else args.cached
+        if not (1 <= ni <= w.max_inflight and 1 <= nc <= w.window_blocks):
+            print("--inflight must be in 1..%d and --cached in 1..%d" % (w.max_inflight, w.window_blocks),
+                  file=sys.stderr)
+            return 2
+        if (ni, nc) != (w.n_inflight, w.n_cached):
+            w = replace(w, name="%s[inflight=%d,cached=%d]" % (w.name, ni, nc), n_inflight=ni, n_cached=nc)
     mode = B.CA_BIDIRECTIONAL if args.mode == "bidirectional" else B.CA_BLOCK_CAUSAL
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -138,7 +152,7 @@ def main() -> int:
         b = state["b"]
         infl = list(range(b, b + C))
         for i, g in enumerate(infl):                                   # a1: publish K/V
-            pool.append(g, timesteps[i] if C == len(timesteps) else 0, 0, k_blocks[i], v_blocks[i])
+            pool.append(g, timesteps[i], 0, k_blocks[i], v_blocks[i])
         pool.rope(q, w.frames_per_block * b, out=q_rot)                # a2
         if i_timed is not None:
             ev[i_timed][0].record()
@@ -146,10 +160,7 @@ def main() -> int:
         if i_timed is not None:
             ev[i_timed][1].record()
         pool.ctx.kv_cache_promote(b)                                   # a7
-        if w.n_cached > 0:
-            pool.ctx.kv_cache_evict(b - w.n_cached)
-        else:
-            pool.ctx.kv_cache_evict(b)
+        pool.ctx.kv_cache_evict(b - w.n_cached)
         state["b"] = b + 1
 
     for _ in range(args.warmup):
@@ -176,7 +187,7 @@ def main() -> int:
         "config": {"workload": w.name, "heads": H, "head_dim": D, "tokens_per_block": L,
                    "inflight_blocks": C, "cached_blocks": w.n_cached, "mode": args.mode,
                    "n_q": C * L, "n_kv": (w.n_cached + C) * L, "flops_per_step": flops,
-                   "step": "5x kv_cache_append + rope3d_apply(Q) + cascade_attn_forward + promote/evict"},
+                   "step": "%dx kv_cache_append + rope3d_apply(Q) + cascade_attn_forward + promote/evict" % C},
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "avg_launch_ms": attn_ms,

@@ -156,6 +156,29 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
  * workgroup walks its whole KV range).  Unknown values are rejected with CA_EINVAL. */
 int32_t ca_set_kernel_variant(ca_ctx* ctx, int32_t variant);
 
+/* ---- Cascade scheduler: the control flow of Algorithm 1, host integers only.
+ * State (b, tau, d) = primary block, timestep index of the primary block, cascade depth.  An
+ * iteration forwards blocks b .. b + min(d, G-1), block b+i at timesteps[tau - i] (older blocks
+ * are cleaner).  timesteps = {t3, t2, t1, t0, tc}: the second-to-last entry is t0 (the step whose
+ * prediction is emitted), the last is the cache step tc.  Only n_parallel == n_timesteps and
+ * n_blocks >= n_parallel are supported (the listing is not self-consistent otherwise). */
+typedef struct ca_sched ca_sched;
+typedef struct {
+  int64_t block_id;
+  int32_t timestep_index;   /* index into timesteps */
+  int32_t timestep;
+} ca_sched_entry;
+
+int32_t ca_sched_create(int64_t n_blocks, int32_t n_parallel, const int32_t* timesteps,
+                        int32_t n_timesteps, ca_sched** out);
+int32_t ca_sched_destroy(ca_sched* s);
+/* The batch of the current iteration, oldest block first; *n_out == 0 once the rollout is over. */
+int32_t ca_sched_batch(const ca_sched* s, ca_sched_entry* out, int32_t cap, int32_t* n_out);
+/* After the forward of the current batch (Alg. 1, lines 12-24): which block ran at t0 and is
+ * emitted (-1 if none), which block completed tc (-1 if none); then advance (b, tau, d). */
+int32_t ca_sched_advance(ca_sched* s, int64_t* emitted_block, int64_t* completed_block);
+int32_t ca_sched_state(const ca_sched* s, int64_t* b, int32_t* tau, int32_t* d, int64_t* iteration);
+
 const char* ca_strerror(int32_t code);
 
 /* Text of the HIP error behind the calling thread's most recent CA_EDEVICE ("" if none). */

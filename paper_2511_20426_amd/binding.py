@@ -28,6 +28,7 @@ EXPORTS = (
     "kv_cache_evict", "kv_cache_retag", "kv_cache_snapshot", "kv_cache_page_index",
     "rope3d_apply", "cascade_attn_forward", "ca_debug_visibility", "ca_set_kernel_variant",
     "ca_strerror", "ca_last_device_error",
+    "ca_sched_create", "ca_sched_destroy", "ca_sched_batch", "ca_sched_advance", "ca_sched_state",
 )
 
 
@@ -45,6 +46,10 @@ class ca_config(C.Structure):
 class ca_slot_info(C.Structure):
     _fields_ = [("slot", C.c_int32), ("state", C.c_int32), ("block_id", C.c_int64),
                 ("timestep", C.c_int32), ("prompt_epoch", C.c_int32)]
+
+
+class ca_sched_entry(C.Structure):
+    _fields_ = [("block_id", C.c_int64), ("timestep_index", C.c_int32), ("timestep", C.c_int32)]
 
 
 class CascadeAttnError(RuntimeError):
@@ -91,6 +96,16 @@ def _load() -> C.CDLL:
                                         C.POINTER(i64), i32, C.POINTER(i32)]
     lib.ca_set_kernel_variant.restype = i32
     lib.ca_set_kernel_variant.argtypes = [vp, i32]
+    lib.ca_sched_create.restype = i32
+    lib.ca_sched_create.argtypes = [i64, i32, C.POINTER(i32), i32, C.POINTER(vp)]
+    lib.ca_sched_destroy.restype = i32
+    lib.ca_sched_destroy.argtypes = [vp]
+    lib.ca_sched_batch.restype = i32
+    lib.ca_sched_batch.argtypes = [vp, C.POINTER(ca_sched_entry), i32, C.POINTER(i32)]
+    lib.ca_sched_advance.restype = i32
+    lib.ca_sched_advance.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
+    lib.ca_sched_state.restype = i32
+    lib.ca_sched_state.argtypes = [vp, C.POINTER(i64), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)]
     lib.ca_strerror.restype = C.c_char_p
     lib.ca_strerror.argtypes = [i32]
     lib.ca_last_device_error.restype = C.c_char_p
@@ -214,3 +229,43 @@ class Context:
 
     def set_kernel_variant(self, variant: int) -> None:
         _check(lib.ca_set_kernel_variant(self._h, variant), "ca_set_kernel_variant")
+
+
+class Scheduler:
+    """Thin owner of a ca_sched* (Algorithm 1 control flow)."""
+
+    def __init__(self, n_blocks: int, n_parallel: int, timesteps: Sequence[int]):
+        ts = (C.c_int32 * len(timesteps))(*timesteps)
+        h = C.c_void_p()
+        _check(lib.ca_sched_create(n_blocks, n_parallel, ts, len(timesteps), C.byref(h)), "ca_sched_create")
+        self._h = h
+
+    def close(self) -> None:
+        if self._h:
+            lib.ca_sched_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def batch(self) -> List[Tuple[int, int, int]]:
+        """[(block_id, timestep_index, timestep)] of the current iteration; [] when done."""
+        buf = (ca_sched_entry * 16)()
+        n = C.c_int32(0)
+        _check(lib.ca_sched_batch(self._h, buf, 16, C.byref(n)), "ca_sched_batch")
+        return [(b.block_id, b.timestep_index, b.timestep) for b in buf[:n.value]]
+
+    def advance(self) -> Tuple[int, int]:
+        """(emitted block or -1, completed block or -1)."""
+        e, c = C.c_int64(-1), C.c_int64(-1)
+        _check(lib.ca_sched_advance(self._h, C.byref(e), C.byref(c)), "ca_sched_advance")
+        return e.value, c.value
+
+    def state(self) -> Tuple[int, int, int, int]:
+        b, it = C.c_int64(), C.c_int64()
+        tau, d = C.c_int32(), C.c_int32()
+        _check(lib.ca_sched_state(self._h, C.byref(b), C.byref(tau), C.byref(d), C.byref(it)), "ca_sched_state")
+        return b.value, tau.value, d.value, it.value

@@ -353,3 +353,62 @@ def test_c5_rollout_ring_buffer():
                 cache.evict(win[0])
         assert [s.astuple() for s in pool.ctx.kv_cache_snapshot()] == cache.snapshot()
     torch.cuda.synchronize()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("mode", [BI, CA])
+def test_algorithm1_rollout_driver(mode):
+    """A full 13-block rollout driven by the library's Alg. 1 scheduler (ramp-up, steady state,
+    drain) on a small token grid, 1 sink block + 2-block window: every output row of every
+    iteration against the oracle, which follows its own transcription of Alg. 1 and its own
+    cache state machine."""
+    import torch
+    from paper_2511_20426_amd.runner import CascadePool
+    from paper_2511_20426_amd.rollout import CascadeRollout
+    w = W.small_variant(W.CONFIGS["c5_wan1p3b_rollout"], heads=2, grid_h=6, grid_w=9, window_blocks=2)
+    L, H = w.block_tokens, w.heads
+    n_blocks = 13
+    _say(f"alg1 rollout driver: L={L} heads={H} mode={mode}")
+    pool = CascadePool.for_workload(w)
+    host, outs = {}, {}
+
+    def qkv_fn(g, ti, it, i):
+        host[(it, i)] = W.draw_step_block(w, it, i, seed=77)
+        return tuple(Hn.to_torch(x, w.dtype) for x in host[(it, i)])
+
+    def out_fn(g, ti, o):
+        outs.setdefault(len(ro.records), []).append(Hn.from_torch(o, w.dtype))
+
+    ro = CascadeRollout(pool, n_blocks, W.TIMESTEPS, qkv_fn, out_fn, mode=mode)
+    trace = orc.algorithm1_trace(n_blocks, 5)
+    assert len(trace) == n_blocks + 4
+    cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, w.max_inflight, w.pages_per_block, H)
+    pos = lambda g: orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w)
+    final_kv = {}
+    worst = 0.0
+    for it, (b, tau, d, batch) in enumerate(trace):
+        rec = ro.step()
+        torch.cuda.synchronize()
+        assert [(g, ti) for g, ti, _ in rec.batch] == batch
+        for i, (g, ti) in enumerate(batch):
+            cache.append(g, W.TIMESTEPS[ti], 0)
+            if ti == len(W.TIMESTEPS) - 1:
+                final_kv[g] = host[(it, i)][1:]
+        infl = [g for g, _ in batch]
+        order, states, _ = cache.kv_order(infl)
+        kb, vb = [], []
+        for g, st in zip(order, states):
+            k, v = host[(it, infl.index(g))][1:] if st == orc.NOISY else final_kv[g]
+            kb.append(orc.rope3d(W.to_f64(k), pos(g), w.rope_dims, w.rope_theta))
+            vb.append(W.to_f64(v))
+        qb = [orc.rope3d(W.to_f64(host[(it, i)][0]), pos(g), w.rope_dims, w.rope_theta)
+              for i, g in enumerate(infl)]
+        ref = orc.cascade_attention(qb, kb, vb, orc.visibility(states, order, infl, mode))
+        got = np.concatenate(outs[it])
+        Hn.assert_close(got, np.concatenate(ref), "bf16", f"alg1 iteration {it}")
+        evicted = orc.rollout_finish(cache, b, [(g, W.TIMESTEPS[ti]) for g, ti in batch])
+        assert rec.completed == (b if tau == 4 else -1)
+        assert rec.evicted == (-1 if evicted is None else evicted)
+        assert [s.astuple() for s in pool.ctx.kv_cache_snapshot()] == cache.snapshot()
+    assert ro.step() is None
+    assert [r.emitted for r in ro.records if r.emitted >= 0] == list(range(n_blocks))

@@ -174,3 +174,44 @@ def test_null_context_is_rejected():
     assert B.lib.ca_pool_bytes(None) == 0
     n = ctypes.c_int32()
     assert B.lib.kv_cache_snapshot(None, None, 0, ctypes.byref(n)) == B.CA_EINVAL
+
+
+def test_scheduler_matches_algorithm1_trace_and_golden():
+    """ca_sched_* against the oracle's transcription of Alg. 1 and the hand-derived fixture."""
+    T = list(W.TIMESTEPS)
+    for n_blocks in (5, 13, 20):
+        tr = orc.algorithm1_trace(n_blocks, 5)
+        s = B.Scheduler(n_blocks, 5, T)
+        emitted, completed = [], []
+        for b, tau, d, batch in tr:
+            assert s.state()[:3] == (b, tau, d)
+            assert s.batch() == [(g, ti, T[ti]) for g, ti in batch]
+            e, c = s.advance()
+            if e >= 0:
+                emitted.append(e)
+            if c >= 0:
+                completed.append(c)
+        assert s.batch() == []                                   # rollout over
+        with pytest.raises(B.CascadeAttnError) as ex:
+            s.advance()
+        assert ex.value.code == B.CA_ESTATE
+        assert emitted == list(range(n_blocks)) and completed == list(range(n_blocks))
+        assert s.state()[3] == n_blocks + 4
+    with open(os.path.join(ROOT, "tests", "golden", "alg1_batch_sizes_B13_G5.txt")) as f:
+        golden = [int(x) for line in f if not line.startswith("#") for x in line.split()]
+    s = B.Scheduler(13, 5, T)
+    sizes = []
+    while True:
+        batch = s.batch()
+        if not batch:
+            break
+        sizes.append(len(batch))
+        s.advance()
+    assert sizes == golden
+    for bad in ((13, 3, T), (3, 5, T)):                          # G != |T|, fewer blocks than G
+        with pytest.raises(B.CascadeAttnError) as ex:
+            B.Scheduler(*bad)
+        assert ex.value.code == B.CA_EUNSUPPORTED
+    with pytest.raises(B.CascadeAttnError) as ex:
+        B.Scheduler(0, 5, T)
+    assert ex.value.code == B.CA_EINVAL
