@@ -21,9 +21,9 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _one_shot(w, mode, scale=None, seed=None, rows=None, heads=None, first_block=0):
+def _one_shot(w, mode, scale=None, seed=None, rows=None, heads=None, first_block=0, k_ramp=None):
     """Cached blocks first_block..first_block+n_cached-1, in-flight ones right after."""
-    q, k, v = W.draw_config(w, seed=seed, scale=scale)
+    q, k, v = W.draw_config(w, seed=seed, scale=scale, k_ramp=k_ramp)
     cached = list(range(first_block, first_block + w.n_cached))
     infl = list(range(first_block + w.n_cached, first_block + w.n_cached + w.n_inflight))
     pool = Hn.gpu_setup(w, k, v, cached, infl)
@@ -170,6 +170,28 @@ def test_bf16_small_full_parity(mode, heads, gh, gw, nc, ni):
     outs, ref = _one_shot(w, mode, seed=22, scale=2.0)
     Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", "small peaked",
                     max_abs=0.12, rel=1.2e-2)
+
+
+@pytest.mark.parametrize("mode", [BI, CA])
+@pytest.mark.parametrize("ramp,bar", [((1.0, 24.0), 2e-2), ((24.0, 1.0), 2e-2), ((1.0, 400.0), 8e-2),
+                                      ((1.0, 400.0, "step"), 8e-2)])
+def test_bf16_moving_row_maximum(mode, ramp, bar):
+    """The running exponent reference has to move: K grows (or shrinks) geometrically along the
+    KV sequence, so the largest logit of a row rises by tens of log2 units over the pages (first
+    case), never rises after the first page (second), or jumps by more than the fp32 exponent
+    range (third, gradually; fourth, from one key to the next: exp2 of a score against a stale
+    reference overflows).  Logits reach |s| ~ 25 (~ 400 in the last two cases), and the bf16
+    rounding of the rotated K alone perturbs such a logit by up to |s| 2^-9 ~ 5e-2 (~ 0.8; a few
+    times less in the root mean square), which the softmax turns into a relative error of that
+    size on the dominant weights: the bars (relative L2 2e-2 and 8e-2, measured 6e-3 and 3e-2)
+    follow from that; what the test guards is the rescaling logic, whose failures are gross (inf,
+    NaN, rows off by factors)."""
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=10, grid_w=13, n_cached=2, n_inflight=2)
+    _say(f"bf16 moving row maximum ramp={ramp} mode={mode}")
+    outs, ref = _one_shot(w, mode, seed=31, k_ramp=ramp)
+    got, want = np.concatenate(outs), np.concatenate(ref)
+    assert np.isfinite(got).all()
+    Hn.assert_close(got, want, "bf16", f"moving maximum {ramp}", max_abs=bar * float(np.abs(want).max()) * 4, rel=bar)
 
 
 def test_bf16_single_block_modes_agree_bitwise():

@@ -132,27 +132,36 @@ def store(x_f32: np.ndarray, dtype: str) -> np.ndarray:
 # --------------------------------------------------------------------------- draws
 
 def draw_qkv(w: Workload, n_q_blocks: int, n_kv_blocks: int, seed: int | None = None,
-             scale: float | None = None):
+             scale: float | None = None, k_ramp: tuple | None = None):
     """Q [n_q_blocks*L,H,D], K and V [n_kv_blocks*L,H,D] in storage dtype.
 
     Draw order Q, K, V from numpy's default_rng(seed), float32 standard normal
     times `scale`.  KV blocks are ordered oldest first: cached blocks, then the
-    in-flight ones; K is pre-RoPE.
+    in-flight ones; K is pre-RoPE.  k_ramp=(a, b): K token n is multiplied by a geometric ramp
+    from a (oldest token) to b (newest), so that the largest logit of a row keeps growing (or
+    shrinking) along the KV sequence; k_ramp=(a, b, "step") switches from a to b half way.
     """
     rng = np.random.default_rng(w.seed if seed is None else seed)
     s = np.float32(w.input_scale if scale is None else scale)
     L, H, D = w.block_tokens, w.heads, w.head_dim
     out = []
-    for nb in (n_q_blocks, n_kv_blocks, n_kv_blocks):
+    for which, nb in enumerate((n_q_blocks, n_kv_blocks, n_kv_blocks)):
         x = rng.standard_normal((nb * L, H, D), dtype=np.float32)
         x *= s
+        if which == 1 and k_ramp is not None:
+            if len(k_ramp) > 2 and k_ramp[2] == "step":      # a for the older half, b for the newer
+                ramp = np.where(np.arange(nb * L) < (nb * L) // 2, k_ramp[0], k_ramp[1]).astype(np.float32)
+            else:
+                ramp = np.geomspace(k_ramp[0], k_ramp[1], nb * L).astype(np.float32)
+            x *= ramp[:, None, None]
         out.append(store(x, w.dtype))
     return tuple(out)
 
 
-def draw_config(w: Workload, seed: int | None = None, scale: float | None = None):
+def draw_config(w: Workload, seed: int | None = None, scale: float | None = None,
+                k_ramp: tuple | None = None):
     """The one-shot configurations: Q for the in-flight blocks, K/V for cached + in-flight."""
-    return draw_qkv(w, w.n_inflight, w.n_cached + w.n_inflight, seed, scale)
+    return draw_qkv(w, w.n_inflight, w.n_cached + w.n_inflight, seed, scale, k_ramp)
 
 
 def draw_step_block(w: Workload, step: int, i: int, seed: int | None = None):
