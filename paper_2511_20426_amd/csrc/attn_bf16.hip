@@ -146,9 +146,10 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     }
   }
 
-  // byte offset of page 0 of KV block i for this head: lane i of (tbl_lo, tbl_hi)
+  // address of page 0 of KV block i for this head: lane i of (tbl_lo, tbl_hi)
   const int my_slot = a.kv_slot[lane & (kMaxKvBlocks - 1)];
-  const uint64_t my_off = (uint64_t(my_slot) * a.pages_per_block * a.heads + h) * uint64_t(kPairBytes);
+  const uint64_t my_off = reinterpret_cast<uint64_t>(a.pool) +
+                          (uint64_t(my_slot) * a.pages_per_block * a.heads + h) * uint64_t(kPairBytes);
   const uint32_t tbl_lo = uint32_t(my_off), tbl_hi = uint32_t(my_off >> 32);
   const uint32_t xo0 = l31 * 256 + ((hi ^ sw) << 4);    // row offset + swizzled chunk 0 (or 1 for hi)
   const uint32_t lane_off = wave * 1024 + lane * 16;   // this lane's 16 bytes inside each 4 KB slice of a page
@@ -164,12 +165,14 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
   for (int i = 0; i < 8; ++i)
     *reinterpret_cast<u32x4*>(lds + kVRing + kPageBytes + (i * 256 + tid) * 16) = u32x4{0, 0, 0, 0};
 
+  // o6/o7 are not early-clobber: the block reads every VGPR input in its first instructions,
+  // before it writes v[96:127], and the inputs need somewhere to live (it uses all of v[128:255])
   f32x16 o0, o1, o2, o3, o4, o5, o6, o7;
   float l0a, l0b, l1a, l1b, negm0, negm1;
   asm volatile(
 #include "attn_core_gfx950.inc"
       : "=&{v[0:15]}"(o0), "=&{v[16:31]}"(o1), "=&{v[32:47]}"(o2), "=&{v[48:63]}"(o3), "=&{v[64:79]}"(o4),
-        "=&{v[80:95]}"(o5), "=&{v[96:111]}"(o6), "=&{v[112:127]}"(o7), "=&{v148}"(l0a), "=&{v149}"(l0b),
+        "=&{v[80:95]}"(o5), "={v[96:111]}"(o6), "={v[112:127]}"(o7), "=&{v148}"(l0a), "=&{v149}"(l0b),
         "=&{v150}"(l1a), "=&{v151}"(l1b), "=&{v184}"(negm0), "=&{v200}"(negm1)
       : "{a[128:143]}"(qt[0]), "{a[144:159]}"(qt[1]), "{a[160:175]}"(qt[2]), "{a[176:191]}"(qt[3]),
         [xo0] "v"(xo0), [lane_off] "v"(lane_off), [tbl_lo] "v"(tbl_lo), [tbl_hi] "v"(tbl_hi),

@@ -4,9 +4,10 @@
 The loop is written as one inline-assembly block (included by attn_bf16.hip) because its speed
 rests on two things a compiler will not hold still for:
 
-  * issue order -- a wave issues in order and an MFMA occupies the matrix pipe for 32 cycles, so
-    every MFMA must be followed by ~28 cycles of independent VALU / LDS issue (the softmax of the
-    previous tile, the operand prefetch) instead of by another MFMA;
+  * issue order -- a wave issues in order, one instruction per 4 cycles, and an MFMA occupies the
+    matrix pipe for 32 cycles: between two MFMAs there is room for exactly 6 more issue quanta
+    (see "issue-slot scheduling" below), and the softmax of the previous tile, the operand
+    prefetch and the page traffic have to be dealt out so that no slot holds more;
   * register files -- Q fragments and the O^T accumulators live in AGPRs, which VALU code never
     touches in the loop; S^T tiles, P^T and the K/V operand fragments live in VGPRs.
 
@@ -17,7 +18,15 @@ Pipeline (a "step" is 32 keys, a page is 4 steps; t counts steps):
     PV(t-1): 16 MFMAs  O^T   += V_frag x P_prev                  (V fragments from LDS)
 The three are independent inside a step.  K and V pages stream global -> LDS (no registers) into
 two 2-page rings; per page there is one barrier that publishes V(q) and frees V(q-1)'s slot
-(step 1, slot 0) and one that publishes K(q+1) and frees K(q)'s slot (step 2, slot 24).
+(before step 1) and one that publishes K(q+1) and frees K(q)'s slot (in step 2).
+
+The exponent reference m_ref of a row is lazy: it starts as the maximum of the row's first tile
+and moves only when it has to.  No maximum is taken in the loop; instead the 16 probabilities a
+lane forms in a step are summed on their own, and a sum above 2^16 (or inf: exp2 against a stale
+reference may overflow) sends the wave to an out-of-line block at the end of the step, which
+takes the tile's maximum, forms the step's probabilities again from the S tile (still in
+registers) against the raised reference and rescales what earlier steps left.  The same branch
+serves the rare step whose S tile needs its ragged tail masked.
 
 Register map (fixed):
   a[0:127]    O^T accumulators, tile (mt, nt) at a[16*(2*mt+nt) ..]
@@ -26,12 +35,14 @@ Register map (fixed):
   v[64:79]    P^T tile A, (nt, kk) at v[64 + 4*(2*nt+kk) ..]      v[80:95]  P^T tile B
   v[96:127]   ring of 8 operand fragments
   v[128:135]  LDS address of chunk pair j in the K ring, v[136:143] the same in the V ring
-  v148..v151  row-sum accumulators (column tile, parity of the element)
+  v148, v150  running row sums of column tile 0 / 1 (v149, v151 stay zero)
+  v152, v153  row sums of the current step, column tile 0 / 1
+  v158..v175  temporaries of the out-of-line blocks
   v[184:199], v[200:215]  -m_ref of column tile 0 / 1, replicated 16 times: the C operand of the
               first MFMA of every S tile, so a tile comes out of the matrix pipe as s*c - m_ref
-  v152..v175  temporaries
   v[216:223]  lane's byte offset inside a page for page load i = 0..7
-  v177,v178   per-KV-block page-0 offsets (lane i = block i), low / high word
+  v[224:255]  the 32 probabilities of the step before they are packed
+  v177,v178   address of page 0 of each KV block for this head (lane i = block i), low / high word
   v179        4*(lane/32): first key row this lane holds in a 32x32 accumulator
   v180        4*(lane ^ 32): ds_bpermute address of the lane holding the other half of this row
 """
@@ -45,7 +56,7 @@ import sys
 # then meaningless; the shipped library is always built with 0.
 ABL = int(os.environ.get("CA_ABL", "0"))
 
-D_AHEAD = 4          # operand fragments are read this many MFMA pairs ahead of use
+D_AHEAD = 5          # operand fragments are read this many MFMA pairs ahead of use
 PAGE = 32768
 VRING = 65536
 
@@ -65,9 +76,9 @@ XOK, XOV = 128, 136
 LACC = 148
 NT = [184, 200]      # -m_ref replicated 16x per column tile
 TMP = 152            # 152..175
-T_FMA = [152, 153]
-PX = [154, 155, 156, 157]
+TS = [152, 153]      # row sums of the current step, per column tile
 MX = [158, 159]
+PX = 224             # 224..255: the 32 probabilities of the step, before packing
 RT = list(range(160, 176))     # rare-path temporaries
 TBLLO, TBLHI, KIDX, XLANE = 177, 178, 179, 180
 DMAOFF = 216         # 216..223: lane's byte offset in a page for load i (+4096 i)
@@ -83,6 +94,9 @@ S_T = 60             # 60..69 temporaries
 S_ADDR = 70          # 70,71
 S_VCC = 72           # 72,73
 S_LDS0 = 74
+S_ADDRV = 76         # 76,77
+S_RG = 78            # 78,79: nonzero if the tile just produced needs its tail masked
+S_VLP = 80           # 80..87: per 32-key step of a page, (-1 if a block's last page is ragged there, 0)
 
 
 class Emitter:
@@ -142,46 +156,50 @@ def tile_max_ops(s_base):
     return ops
 
 
-def emit_page_address(E, which, advance):
-    """Scalar part of a page request: move the (block, page) cursor of the K (which=0) or V
-    (which=1) stream on by one page -- staying on the last visible page once the end is reached
-    (the extra copies are never read) -- and leave the page's global address in s[S_ADDR:+1]."""
-    kb, pg = (S_KKB, S_KPG) if which == 0 else (S_VKB, S_VPG)
-    t = S_T
-    if advance:
-        E.e(f"s_add_u32 s{t}, s{pg}, 1")                         # pg + 1
-        E.e(f"s_cmp_eq_u32 s{t}, s{S_P}")
-        E.e(f"s_cselect_b32 s{t}, 0, s{t}")                      # wrapped page
-        E.e(f"s_addc_u32 s{t + 1}, s{kb}, 0")                    # kb + (wrapped ? 1 : 0): scc still set by cmp
-        E.e(f"s_cmp_lt_u32 s{t + 1}, s{S_NKVB}")                 # still inside the visible blocks?
-        E.e(f"s_cselect_b32 s{pg}, s{t}, s{pg}")
-        E.e(f"s_cselect_b32 s{kb}, s{t + 1}, s{kb}")
-    # 64-bit byte offset: table[kb] + pg*stride + which*PAGE, then + pool base
-    E.e(f"v_readlane_b32 s{t + 2}, {V(TBLLO)}, s{kb}")
-    E.e(f"v_readlane_b32 s{t + 3}, {V(TBLHI)}, s{kb}")
-    E.e(f"s_mul_i32 s{t + 4}, s{pg}, s{S_STRIDE}")
-    E.e(f"s_mul_hi_u32 s{t + 5}, s{pg}, s{S_STRIDE}")
-    E.e(f"s_add_u32 s{t + 2}, s{t + 2}, s{t + 4}")
-    E.e(f"s_addc_u32 s{t + 3}, s{t + 3}, s{t + 5}")
-    if which:
-        E.e(f"s_add_u32 s{t + 2}, s{t + 2}, {PAGE}")
-        E.e(f"s_addc_u32 s{t + 3}, s{t + 3}, 0")
-    E.e(f"s_add_u32 s{S_ADDR}, s{S_POOL}, s{t + 2}")
-    E.e(f"s_addc_u32 s{S_ADDR + 1}, s{S_POOL + 1}, s{t + 3}")
+def page_advance_lines():
+    """Moves the page cursor (kb, pg) on by one page -- staying on the last visible page once the
+    end is reached (the extra copies are never read) -- and leaves the K page's global address in
+    s[S_ADDR:+1]; the V page of the same pair is PAGE bytes further.  Returned as groups of lines
+    that must stay contiguous (each group hands a condition over in SCC)."""
+    kb, pg, t = S_KKB, S_KPG, S_T
+    return [
+        [f"s_add_u32 s{t}, s{pg}, 1", f"s_cmp_eq_u32 s{t}, s{S_P}", f"s_cselect_b32 s{t}, 0, s{t}",
+         f"s_addc_u32 s{t + 1}, s{kb}, 0"],                      # kb + (wrapped ? 1 : 0): scc from the cmp
+        [f"s_cmp_lt_u32 s{t + 1}, s{S_NKVB}", f"s_cselect_b32 s{pg}, s{t}, s{pg}",
+         f"s_cselect_b32 s{kb}, s{t + 1}, s{kb}"],
+    ] + page_address_lines()
 
 
-def emit_page_load(E, i, lds_slot_off):
-    """Load number i (0..7) of the requested page: 64 lanes x 16 B -> 1 KB of LDS at
-    slot + 4096 i + 1024 wave (M0 carries the LDS address, the VGPR the byte offset in the page)."""
-    E.e(f"s_add_u32 m0, s{S_M0B}, {lds_slot_off + 4096 * i}")
+def page_address_lines():
+    kb, pg, t = S_KKB, S_KPG, S_T
+    return [
+        [f"v_readlane_b32 s{t + 2}, {V(TBLLO)}, s{kb}"],
+        [f"v_readlane_b32 s{t + 3}, {V(TBLHI)}, s{kb}"],
+        [f"s_mul_i32 s{t + 4}, s{pg}, s{S_STRIDE}"],
+        [f"s_mul_hi_u32 s{t + 5}, s{pg}, s{S_STRIDE}"],
+        [f"s_add_u32 s{S_ADDR}, s{t + 2}, s{t + 4}", f"s_addc_u32 s{S_ADDR + 1}, s{t + 3}, s{t + 5}"],
+    ]
+
+
+def v_address_lines():
+    """V page of the pair whose K address is in s[S_ADDR:+1]."""
+    return [[f"s_add_u32 s{S_ADDRV}, s{S_ADDR}, {PAGE}", f"s_addc_u32 s{S_ADDRV + 1}, s{S_ADDR + 1}, 0"]]
+
+
+def page_load_lines(i, lds_slot_off, which):
+    """Load number i (0..7) of a page: 64 lanes x 16 B -> 1 KB of LDS at slot + 4096 i + 1024 wave
+    (M0 carries the LDS address, the VGPR the byte offset in the page)."""
+    lines = [f"s_add_u32 m0, s{S_M0B}, {lds_slot_off + 4096 * i}"]
     if not ABL & 4:
-        E.e(f"global_load_lds_dwordx4 {V(DMAOFF + i)}, s[{S_ADDR}:{S_ADDR + 1}]")
+        a = S_ADDRV if which else S_ADDR
+        lines.append(f"global_load_lds_dwordx4 {V(DMAOFF + i)}, s[{a}:{a + 1}]")
+    return lines
 
 
-def emit_issue_page(E, which, lds_slot_off, advance):
-    emit_page_address(E, which, advance)
+def emit_issue_page(E, which, lds_slot_off):
     for i in range(8):
-        emit_page_load(E, i, lds_slot_off)
+        for ln in page_load_lines(i, lds_slot_off, which):
+            E.e(ln)
 
 
 def emit_mask(E, s_base, valid_sreg):
@@ -271,107 +289,287 @@ def p_word(p_base, j):
     return p_base + 4 * (2 * nt + (e >> 3)) + ((e & 7) >> 1)
 
 
-def emit_pack(E, j, p_cur):
-    """elements j-1, j -> one bf16 pair of P^T (round to nearest even)."""
-    E.e(f"v_cvt_pk_bf16_f32 {V(p_word(p_cur, j))}, {V(PX[(j - 1) & 3])}, {V(PX[j & 3])}")
+# ---------------------------------------------------------------------------- issue-slot scheduling
+# Measured on gfx950 with one wave per SIMD: the wave issues one instruction per 4 cycles
+# whatever its kind; an MFMA 32x32x16 holds the issue port for 8 cycles and the matrix pipe for
+# 32, so the 32 cycles from one MFMA to the next have room for 6 more issue quanta of 4 cycles.
+# v_exp_f32 takes 2 quanta, ds_read_b128 2.2, v_readlane 2, a global->LDS load 2.7, a branch that
+# is not taken 2.5 (5 if it directly follows the instruction that sets its condition), everything
+# else (VALU, SALU, s_waitcnt, s_nop) 1.  Whatever exceeds 8 quanta between two MFMAs delays the
+# second one by the full excess; there is no carry-over of slack between slots.
+CAP = 8.0
 
 
-def emit_rowsum(E, j, p_cur):
-    """row sums += the two (unrounded) probabilities of the pair ending at element j: one
-    accumulator for even, one for odd elements of each column tile.  (A v_dot2_f32_bf16 on the packed
-    pair would halve the instruction count but measured 2.3 ms slower per forward.)"""
-    nt = j >> 4
-    E.e(f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(PX[(j - 1) & 3])}")
-    E.e(f"v_add_f32 {V(LACC + 2 * nt + 1)}, {V(LACC + 2 * nt + 1)}, {V(PX[j & 3])}")
+def quanta(line):
+    op = line.split()[0]
+    if op.endswith(":") or op.startswith(";"):
+        return 0.0
+    if op.startswith("v_mfma"):
+        return 2.0
+    if op.startswith("v_exp"):
+        return 2.0
+    if op.startswith("ds_read_b128"):
+        return 2.2
+    if op.startswith("v_readlane"):
+        return 2.0
+    if op.startswith("global_load"):
+        return 2.7
+    if op.startswith("s_cbranch"):
+        return 2.5
+    return 1.0
 
 
-def exp_slot(e):
-    """Issue slot of the exponential of element e (0..31) of the tile: two each in slots 0 and 1,
-    then one per slot, so that the last one issues in slot 29 and everything derived from it
-    (pack, row sum) still fits under the step's last MFMAs."""
-    return e >> 1 if e < 4 else e - 2
+class Atom:
+    """Instructions that stay together, with the earliest slot they may issue in (`ready`, or
+    `gap` slots after the latest of the atoms in `after`) and the slot they should issue by."""
+    def __init__(self, lines, ready=0, deadline=31, after=(), gap=0, tag=None, hard=31):
+        self.lines = list(lines)
+        self.cost = sum(quanta(l) for l in self.lines)
+        self.ready, self.deadline, self.tag, self.hard = ready, deadline, tag, hard
+        self.after = [(a, gap) for a in after]            # (atom, slots that must lie between)
+        self.slot = None
+
+    def ready_slot(self):
+        r = self.ready
+        for a, gap in self.after:
+            if a.slot is None:
+                return None
+            r = max(r, a.slot + gap)
+        return r
 
 
-def emit_step(E, R, par):
+def schedule(fixed_load, atoms):
+    """Earliest-deadline-first list scheduling of `atoms` into the 32 slots of a step.
+    fixed_load[i]: quanta already spoken for in slot i.  Returns per-slot lists of atoms."""
+    placed = [[] for _ in range(32)]
+    pending = list(atoms)
+    for i in range(32):
+        cap = CAP - fixed_load[i]
+        while True:
+            cands = [a for a in pending if a.ready_slot() is not None and a.ready_slot() <= i]
+            cands.sort(key=lambda a: a.deadline)
+            pick = None
+            for a in cands:
+                if a.cost <= cap + 1e-9 or a.hard <= i:
+                    pick = a
+                    break
+            if pick is None:
+                break
+            pick.slot = i
+            placed[i].append(pick)
+            pending.remove(pick)
+            cap -= pick.cost
+    assert not pending, [a.lines for a in pending]
+    return placed
+
+
+THRESH = "0x47800000"     # 2^16: a step's row sum of 16 probabilities above this moves the reference
+K_BARRIER_SLOT = 16       # step 2: K(q+1) visible, slot of K(q) free
+N_KLOADS_R2 = 2           # of the 8 loads of K(q+2), how many issue in step 2 (the rest in step 3)
+
+
+def build_step(R, par):
+    """One 32-key step as a list of 32 slots: (MFMA line, [lines issued after it])."""
     cur, nxt = ("A", "B") if R % 2 == 0 else ("B", "A")
     s_cur, s_next = S_TILE[cur], S_TILE[nxt]
     p_prev, p_cur = (P_TILE["B"], P_TILE["A"]) if R % 2 == 0 else (P_TILE["A"], P_TILE["B"])
     nR, npar = ((R + 1) & 3, par if R < 3 else 1 - par)
-    max_ops = tile_max_ops(s_next)
-    max_at = {}                                           # slot -> ops (slots 18..29: QK retired)
-    for k, op in enumerate(max_ops):
-        max_at.setdefault(18 + (k * 12) // 16, []).append(op)
-    exps_at, packs_at = {}, {}
-    for e in range(32):
-        exps_at.setdefault(exp_slot(e), []).append(e)
-        if e & 1:                                         # a trans result is consumed >= 2 slots later
-            packs_at.setdefault(exp_slot(e) + 2, []).append(e)
-    px_holds = {}                                         # PX register -> element, to check the ring
+    cold, back = f"COLD_{R}_{par}_%=", f"BACK_{R}_{par}_%="
 
-    E.e(f"; ---- step R={R} parity={par}")
+    mfma, head, tail = [None] * 32, [[] for _ in range(32)], [[] for _ in range(32)]
     for i in range(32):
         f, nt = i >> 1, i & 1
-        if R == 1 and i == 0:                             # V(q) visible; slot of V(q-1) free -> V(q+1)
-            E.e("s_waitcnt vmcnt(8)")
-            if not ABL & 8:
-                E.e("s_barrier")
-            emit_page_address(E, 1, advance=True)
-        if R == 2 and i == 24:                            # K(q+1) visible; slot of K(q) free -> K(q+2)
-            E.e("s_waitcnt vmcnt(8)")
-            if not ABL & 8:
-                E.e("s_barrier")
-            emit_page_address(E, 0, advance=True)
-        if nt == 0 and not ABL & 2:
-            E.e(f"s_waitcnt lgkmcnt({D_AHEAD - 1})")      # fragment f has landed
         if f < 8:
-            E.e(mfma_qk(f == 0, s_next, nt, f, f))
+            mfma[i] = mfma_qk(f == 0, s_next, nt, f, f)
         else:
             g = f - 8
-            E.e(mfma_pv(g & 3, nt, f, p_prev, g >> 2))
-        # fillers: page load, operand prefetch, softmax of s_cur, running max of s_next
-        if R == 1 and i < 8:
-            emit_page_load(E, i, VRING + (1 - par) * PAGE)
-        if R == 2 and i >= 24:
-            emit_page_load(E, i - 24, par * PAGE)
-        if nt == 0 and not ABL & 2:
+            mfma[i] = mfma_pv(g & 3, nt, f, p_prev, g >> 2)
+        if nt == 0 and not ABL & 2:                        # operand prefetch, D_AHEAD pairs ahead
             fa = f + D_AHEAD
-            if fa < 16:
-                E.e(ds_read_frag(fa, frag_source(R, par, fa)))
+            src = frag_source(R, par, fa) if fa < 16 else frag_source(nR, npar, fa - 16)
+            head[i].append(ds_read_frag(fa % 16, src))
+        # what must precede the next MFMA: every other pair waits for its two fragments
+        if (i + 1) % 4 == 0 and not ABL & 2:
+            tail[i].append(f"s_waitcnt lgkmcnt({D_AHEAD - 2})")
+    if R == 0:                                             # before step 1: V(q) visible, V(q-1)'s slot free
+        tail[31] += ["s_waitcnt vmcnt(@VMCNT_V@)"] + ([] if ABL & 8 else ["s_barrier"])
+    if R == 2:
+        tail[K_BARRIER_SLOT - 1] += ["s_waitcnt vmcnt(@VMCNT_K@)"] + ([] if ABL & 8 else ["s_barrier"])
+
+    atoms = []
+    if not ABL & 1:
+        # row sums of the previous step join the running sums; this step's start afresh
+        lacc = [Atom([f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(TS[nt])}"], 0, 0, hard=1) for nt in range(2)]
+        atoms += lacc
+        exps = [Atom([f"v_exp_f32 {V(PX + e)}, {V(s_cur + e)}"], 0, (e * 22) // 32, hard=26) for e in range(32)]
+        atoms += exps
+        last_sum = [None, None]
+        for j in range(1, 32, 2):
+            nt = j >> 4
+            deps, dl = [exps[j - 1], exps[j]], (j * 22) // 32 + 5
+            atoms.append(Atom([f"v_cvt_pk_bf16_f32 {V(p_word(p_cur, j))}, {V(PX + j - 1)}, {V(PX + j)}"],
+                              0, dl, deps, 2, hard=29))
+            if last_sum[nt] is None:
+                sm = [Atom([f"v_add_f32 {V(TS[nt])}, {V(PX + j - 1)}, {V(PX + j)}"], 0, dl, deps, 2, hard=28)]
+                sm[0].after.append((lacc[nt], 0))
             else:
-                E.e(ds_read_frag(fa - 16, frag_source(nR, npar, fa - 16)))
-        if ABL & 1:
-            continue
-        for j in packs_at.get(i, []):
-            assert px_holds[PX[(j - 1) & 3]] == j - 1 and px_holds[PX[j & 3]] == j
-            emit_pack(E, j, p_cur)
-            emit_rowsum(E, j, p_cur)
-        for e in exps_at.get(i, []):
-            px_holds[PX[e & 3]] = e
-            E.e(f"v_exp_f32 {V(PX[e & 3])}, {V(s_cur + 16 * (e >> 4) + (e & 15))}")
-        for op in max_at.get(i, []):
-            E.e(op)
-        # the tile just produced is exponentiated in the next step: mask its ragged tail (slot 30),
-        # then settle the exponent reference (after the last MFMA)
-        if i == 30:
-            if R < 3:
-                emit_mask_check(E, s_next, S_PGCUR, R + 1)
-            else:
-                emit_mask_check(E, s_next, S_PGNEXT, 0)
-    if ABL & 1:
-        return
-    emit_settle(E, s_next, p_cur)
+                sm = [Atom([f"v_add_f32 {V(TS[nt])}, {V(TS[nt])}, {V(PX + k)}"], 0, dl, deps, 2, hard=28)
+                      for k in (j - 1, j)]
+                sm[0].after.append((last_sum[nt], 0))
+                sm[1].after.append((sm[0], 0))
+            atoms += sm
+            last_sum[nt] = sm[-1]
+        # is the tile just produced the ragged tail of a block's last page?
+        pg, sub = (S_PGCUR, R + 1) if R < 3 else (S_PGNEXT, 0)
+        rag = Atom([f"s_cmp_eq_u32 s{pg}, s{S_PM1}",
+                    f"s_cselect_b64 s[{S_RG}:{S_RG + 1}], s[{S_VLP + 2 * sub}:{S_VLP + 2 * sub + 1}], 0"], 0, 6, hard=24)
+        det = Atom([f"v_max_f32 {V(RT[1])}, {V(TS[0])}, {V(TS[1])}",
+                    f"v_cmp_lt_f32 vcc, {THRESH}, {V(RT[1])}"], 0, 28, [last_sum[0], last_sum[1]], 0, hard=29)
+        # scc travels from here to the branch after the last MFMA: nothing that writes scc may
+        # issue in slots 30 and 31 (every such atom has hard <= 29)
+        orr = Atom([f"s_or_b64 s[{S_T + 8}:{S_T + 9}], vcc, s[{S_RG}:{S_RG + 1}]"], 30, 30, [det, rag], 1, hard=30)
+        atoms += [rag, det, orr]
+        tail[31].insert(0, f"{back}:")
+        tail[31].insert(0, f"s_cbranch_scc1 {cold}")
+    else:
+        rag = None
+    # page traffic
+    loads = []
+    if R == 0:                                             # address of V(q+1), then of K(q+2)
+        prev = None
+        for k, grp in enumerate(v_address_lines() + page_advance_lines()):
+            prev = Atom(grp, 2, 6 + 3 * k, [prev] if prev else [], 0, hard=29)
+            atoms.append(prev)
+    if R == 1:                                             # V(q+1) into the slot V(q-1) left
+        for i in range(8):
+            loads.append(Atom(page_load_lines(i, VRING + (1 - par) * PAGE, 1), 0, 2 + 4 * i, tag=("load", 1), hard=29))
+    if R == 2:                                             # K(q+2) into the slot K(q) left
+        for i in range(N_KLOADS_R2):
+            loads.append(Atom(page_load_lines(i, par * PAGE, 0), K_BARRIER_SLOT,
+                              K_BARRIER_SLOT + 2 + (i * (26 - K_BARRIER_SLOT)) // N_KLOADS_R2, tag=("load", 0), hard=29))
+    if R == 3:
+        n = 8 - N_KLOADS_R2
+        for i in range(n):
+            loads.append(Atom(page_load_lines(N_KLOADS_R2 + i, par * PAGE, 0), 0, 2 + (i * 28) // n, tag=("load", 0), hard=29))
+        # page-in-block counters of pages q and q+1 move on; one page less to go
+        pe = Atom([f"s_mov_b32 s{S_PGCUR}, s{S_PGNEXT}", f"s_add_u32 s{S_T}, s{S_PGNEXT}, 1",
+                   f"s_cmp_eq_u32 s{S_T}, s{S_P}", f"s_cselect_b32 s{S_PGNEXT}, 0, s{S_T}",
+                   f"s_sub_u32 s{S_NLEFT}, s{S_NLEFT}, 1"], 0, 20, [rag] if rag else [], 1, hard=29)
+        atoms.append(pe)
+    atoms += loads
+
+    fixed = [2.0 + sum(quanta(l) for l in head[i] + tail[i]) for i in range(32)]
+    placed = schedule(fixed, atoms)
+    for i in (30, 31):
+        for a in placed[i]:
+            assert not any(l.split()[0].startswith(("s_add", "s_sub", "s_cmp", "s_and", "s_mul")) for l in a.lines), a.lines
+    slots = []
+    for i in range(32):
+        lines = list(head[i])
+        for a in placed[i]:
+            lines += a.lines
+        lines += tail[i]
+        slots.append((mfma[i], lines))
+    return slots, (s_cur, s_next, p_cur, cold, back, (S_VLAST + (R + 1 if R < 3 else 0)))
 
 
-def emit_page_end(E):
-    """Per-page scalar bookkeeping: page-in-block counters of pages q and q+1."""
-    E.e(f"s_mov_b32 s{S_PGCUR}, s{S_PGNEXT}")
-    E.e(f"s_add_u32 s{S_T}, s{S_PGNEXT}, 1")
-    E.e(f"s_cmp_eq_u32 s{S_T}, s{S_P}")
-    E.e(f"s_cselect_b32 s{S_PGNEXT}, 0, s{S_T}")
+def emit_cold(E, s_cur, s_next, p_cur, cold, back, valid_sreg):
+    """Out-of-line end of a step, entered when some lane's row sum of the step crossed THRESH
+    (vcc) or the tile just produced needs its ragged tail masked (s[S_RG]).
+
+    Moving the reference: the probabilities of the step were formed against a reference that
+    turned out too low (they may even have overflowed), so they are formed again from the S tile,
+    which is still in registers: the row maximum relative to the old reference gives the shift
+    delta >= 0; row sums and accumulators (all from earlier steps) are scaled by 2^-delta, the
+    tile just produced and the -m_ref operand move by delta."""
+    c = E.cold
+    skip_ovf, done = E.label("NOOVF"), E.label("CDONE")
+    c.append(f"{cold}:")
+    c.append("s_nop 15\ns_nop 15\ns_nop 15")            # every MFMA issued so far has written back
+    c.append(f"s_cbranch_vccz {skip_ovf}")
+    for nt in range(2):
+        b = s_cur + 16 * nt
+        m, other, delta, alpha = V(MX[nt]), V(RT[3]), V(RT[4]), V(RT[6])
+        c.append(f"v_max3_f32 {m}, {V(b)}, {V(b + 1)}, {V(b + 2)}")
+        for k in range(6):
+            c.append(f"v_max3_f32 {m}, {m}, {V(b + 3 + 2 * k)}, {V(b + 4 + 2 * k)}")
+        c.append(f"v_max_f32 {m}, {m}, {V(b + 15)}")
+        c.append(f"ds_bpermute_b32 {other}, {V(XLANE)}, {m}")       # the partner lane's (lane ^ 32) maximum
+        c.append("s_waitcnt lgkmcnt(0)")
+        c.append(f"v_max_f32 {delta}, {m}, {other}")
+        c.append(f"v_max_f32 {delta}, 0, {delta}")                  # the reference never moves down
+        c.append(f"v_exp_f32_e64 {alpha}, -{delta}")
+        c.append("s_nop 3")                              # a trans result is not forwarded to the next VALU op
+        c.append(f"v_mul_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {alpha}")
+        for mt in range(4):
+            for i in range(16):
+                acc = A(16 * (2 * mt + nt) + i)
+                tmp = V(RT[8 + (i % 8)])
+                c.append(f"v_accvgpr_read_b32 {tmp}, {acc}")
+                c.append(f"v_mul_f32 {tmp}, {tmp}, {alpha}")
+                c.append(f"v_accvgpr_write_b32 {acc}, {tmp}")
+        for i in range(16):                              # the step's probabilities again
+            c.append(f"v_sub_f32 {V(b + i)}, {V(b + i)}, {delta}")
+        for i in range(16):
+            c.append(f"v_exp_f32 {V(PX + 16 * nt + i)}, {V(b + i)}")
+        c.append("s_nop 3")
+        c.append(f"v_add_f32 {V(TS[nt])}, {V(PX + 16 * nt)}, {V(PX + 16 * nt + 1)}")
+        for i in range(2, 16):
+            c.append(f"v_add_f32 {V(TS[nt])}, {V(TS[nt])}, {V(PX + 16 * nt + i)}")
+        for j in range(16 * nt + 1, 16 * nt + 16, 2):
+            c.append(f"v_cvt_pk_bf16_f32 {V(p_word(p_cur, j))}, {V(PX + j - 1)}, {V(PX + j)}")
+        for i in range(16):                              # -m_ref operand and the tile just produced
+            c.append(f"v_sub_f32 {V(NT[nt] + i)}, {V(NT[nt] + i)}, {delta}")
+            c.append(f"v_sub_f32 {V(s_next + 16 * nt + i)}, {V(s_next + 16 * nt + i)}, {delta}")
+    c.append(f"{skip_ovf}:")
+    c.append(f"s_cmp_eq_u32 s{S_RG}, 0")
+    c.append(f"s_cbranch_scc1 {done}")
+    sub_e = Emitter()
+    emit_mask(sub_e, s_next, valid_sreg)
+    c.extend(sub_e.lines)
+    c.append(f"{done}:")
+    c.append("s_nop 7")
+    c.append(f"s_branch {back}")
+
+
+def emit_step(E, R, par, vmcnt):
+    slots, cold_args = build_step(R, par)
+    E.e(f"; ---- step R={R} parity={par}")
+    for m, lines in slots:
+        E.e(m)
+        for ln in lines:
+            E.e(ln.replace("@VMCNT_V@", str(vmcnt[0])).replace("@VMCNT_K@", str(vmcnt[1])))
+    if not ABL & 1:
+        emit_cold(E, *cold_args)
+
+
+def wait_counts():
+    """vmcnt operands of the two page barriers: loads complete in issue order, so waiting for
+    page X means allowing as many loads in flight as are issued after X's last one."""
+    order = []                                            # (R, slot, stream) of every load of one page period
+    for R in range(4):
+        slots, _ = build_step(R, 0)
+        for i, (_, lines) in enumerate(slots):
+            for ln in lines:
+                if ln.startswith("s_add_u32 m0"):
+                    order.append((R, i, 1 if R == 1 else 0))
+    assert len(order) == 16, order
+    def after_last(stream, until):
+        """loads issued after the last `stream` load of the previous page, up to time `until` of this page"""
+        last = max(k for k, o in enumerate(order) if o[2] == stream)
+        n_prev = len(order) - 1 - last
+        n_now = sum(1 for o in order if (o[0], o[1]) <= until)
+        return n_prev + n_now
+    vm_v = after_last(1, (0, 31))                         # barrier in the tail of step 0
+    vm_k = after_last(0, (2, K_BARRIER_SLOT - 1))
+    assert vm_v < 60 and vm_k < 60
+    return vm_v, vm_k
 
 
 def emit_drain(E, par_last):
     """PV of the final step: V page (parity par_last), keys 96..127, P tile B."""
+    for nt in range(2):                                   # row sums of the final step
+        E.e(f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(TS[nt])}")
     for g in range(8):
         mt, kk = g & 3, g >> 2
         E.e(f"ds_read_b128 {V(FR + 4 * g, 4)}, {V(XOV + 6 + kk)} offset:{par_last * PAGE + mt * 8192}")
@@ -398,6 +596,10 @@ def generate():
         E.e(f"s_sub_i32 s{S_VLAST + sub}, s{S_LASTV}, {32 * sub}")
         E.e(f"s_max_i32 s{S_VLAST + sub}, s{S_VLAST + sub}, 0")
         E.e(f"s_min_i32 s{S_VLAST + sub}, s{S_VLAST + sub}, 32")
+    for sub in range(4):                                  # (-1, 0) where a last page is ragged
+        E.e(f"s_cmp_lt_u32 s{S_VLAST + sub}, 32")
+        E.e(f"s_cselect_b32 s{S_VLP + 2 * sub}, -1, 0")
+        E.e(f"s_mov_b32 s{S_VLP + 2 * sub + 1}, 0")
     for i in range(8):
         E.e(f"v_add_u32 {V(DMAOFF + i)}, {4096 * i}, %[lane_off]")
     E.e(f"v_mov_b32 {V(TBLLO)}, %[tbl_lo]")
@@ -412,6 +614,8 @@ def generate():
         E.e(f"v_accvgpr_write_b32 {A(r)}, 0")
     for r in range(4):
         E.e(f"v_mov_b32 {V(LACC + r)}, 0")
+    for nt in range(2):
+        E.e(f"v_mov_b32 {V(TS[nt])}, 0")
     for nt in range(2):                                   # m_ref = 0 until tile 0 has been seen
         for i in range(16):
             E.e(f"v_mov_b32 {V(NT[nt] + i)}, 0")
@@ -422,14 +626,18 @@ def generate():
     E.e(f"s_add_u32 s{S_T}, s{S_PGCUR}, 1")
     E.e(f"s_cmp_eq_u32 s{S_T}, s{S_P}")
     E.e(f"s_cselect_b32 s{S_PGNEXT}, 0, s{S_T}")
-    for r in (S_KKB, S_VKB):
-        E.e(f"s_mov_b32 s{r}, %[kb0]")
-    for r in (S_KPG, S_VPG):
-        E.e(f"s_mov_b32 s{r}, %[pg0]")
+    E.e(f"s_mov_b32 s{S_KKB}, %[kb0]")
+    E.e(f"s_mov_b32 s{S_KPG}, %[pg0]")
     # ---- K(0), V(0), K(1) in flight; wait for the first two, publish
-    emit_issue_page(E, 0, 0, advance=False)
-    emit_issue_page(E, 1, VRING, advance=False)
-    emit_issue_page(E, 0, PAGE, advance=True)
+    for grp in page_address_lines() + v_address_lines():
+        for ln in grp:
+            E.e(ln)
+    emit_issue_page(E, 0, 0)
+    emit_issue_page(E, 1, VRING)
+    for grp in page_advance_lines():
+        for ln in grp:
+            E.e(ln)
+    emit_issue_page(E, 0, PAGE)
     E.e("s_waitcnt vmcnt(8) lgkmcnt(0)")
     E.e("s_barrier")
     # ---- S tile of step 0 into tile A, its mask, max and reference
@@ -447,17 +655,18 @@ def generate():
     # first operand fragments of step (R=0, parity 0)
     for f in range(D_AHEAD):
         E.e(ds_read_frag(f, frag_source(0, 0, f)))
+    E.e(f"s_waitcnt lgkmcnt({D_AHEAD - 2})")
 
     # ---- main loop, two pages per trip (ring parity is compile-time)
     loop, exit_even, exit_odd, done = (E.label("LOOP"), E.label("EXIT_EVEN"), E.label("EXIT_ODD"),
                                         E.label("DONE"))
+    vmcnt = wait_counts()
     E.e(f"{loop}:")
     for par in range(2):
         for R in range(4):
-            emit_step(E, R, par)
-        emit_page_end(E)
-        E.e(f"s_sub_u32 s{S_NLEFT}, s{S_NLEFT}, 1")
+            emit_step(E, R, par, vmcnt)
         E.e(f"s_cmp_eq_u32 s{S_NLEFT}, 0")
+        E.e("s_nop 0")
         E.e(f"s_cbranch_scc1 {exit_even if par == 0 else exit_odd}")
     E.e(f"s_branch {loop}")
     E.e(f"{exit_even}:")
@@ -490,7 +699,7 @@ def main(out_path):
         for t in text:
             f.write('"' + t.replace("\\", "\\\\").replace('"', '\\"') + '\\n"\n')
     # registers the block uses beyond its operands (v148..v151 are outputs)
-    clob = [f"v{i}" for i in range(128, 224) if not 148 <= i <= 151 and i not in (184, 200)] + [f"a{i}" for i in range(0, 128)] + [f"s{i}" for i in range(36, 96)]
+    clob = [f"v{i}" for i in range(128, 256) if not 148 <= i <= 151 and i not in (184, 200)] + [f"a{i}" for i in range(0, 128)] + [f"s{i}" for i in range(36, 96)]
     clob_path = out_path.replace("attn_core_gfx950.inc", "attn_core_clobbers.inc")
     with open(clob_path, "w") as f:
         f.write("// Generated by gen_attn_core.py -- do not edit.\n#define CA_CORE_CLOBBERS \\\n")
