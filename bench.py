@@ -194,6 +194,16 @@ def main() -> int:
                      "traffic": ATTN_TRAFFIC_BYTES_C4 if (w.name == "c4_wan14b_cascade5" and
                                                           mode == B.CA_BIDIRECTIONAL) else None},
     }
+    # what the matrix pipes sustain on this machine with nothing else in the loop (the nominal peak
+    # assumes 2.4 GHz; under a full MFMA load with toggling operands the chip clocks lower)
+    probe = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream(dev).cuda_stream
+    rnd = B.mfma_microbench(1, 100000, probe.data_ptr(), probe.numel(), stream)
+    zer = B.mfma_microbench(0, 100000, probe.data_ptr(), probe.numel(), stream)
+    result["roofline"]["mfma_only_microbench"] = {
+        "random_operands": {"TFLOP/s": rnd[0], "clock_GHz": rnd[1]},
+        "zero_operands": {"TFLOP/s": zer[0], "clock_GHz": zer[1]},
+        "achieved_over_random_operands": achieved / rnd[0]}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result))

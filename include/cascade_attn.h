@@ -156,6 +156,15 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
  * workgroup walks its whole KV range).  Unknown values are rejected with CA_EINVAL. */
 int32_t ca_set_kernel_variant(ca_ctx* ctx, int32_t variant);
 
+/* Measurement aid, not a step of the method: runs v_mfma_f32_32x32x16_bf16 back to back on every
+ * CU (nothing else in the loop) and reports the sustained dense bf16 rate and the shader clock the
+ * chip held meanwhile -- the practical ceiling to read cascade_attn_forward's TFLOP/s against.
+ * data_kind 0: all-zero operands, 1: pseudo-random bf16 operands (more switching, lower clock).
+ * trips: loop trips of 32 MFMAs per wave (100000 runs ~15 ms).  scratch_dev: device memory, at
+ * least 16 bytes per CU, overwritten.  Synchronises the stream.  Either output may be NULL. */
+int32_t ca_mfma_microbench(int32_t data_kind, int32_t trips, void* scratch_dev, size_t scratch_bytes,
+                           void* hip_stream, double* tflops, double* clock_ghz);
+
 /* ---- Cascade scheduler: the control flow of Algorithm 1, host integers only.
  * State (b, tau, d) = primary block, timestep index of the primary block, cascade depth.  An
  * iteration forwards blocks b .. b + min(d, G-1), block b+i at timesteps[tau - i] (older blocks

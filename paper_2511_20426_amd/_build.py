@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.environ.get("CASCADE_ATTN_LIB") or os.path.join(PKG, "libcascade_attn.so")
 
-SOURCES = ["ca_meta.cpp", "ca_api.cpp", "ca_sched.cpp", "rope_cache.hip", "attn_f32.hip", "attn_bf16.hip"]
+SOURCES = ["ca_meta.cpp", "ca_api.cpp", "ca_sched.cpp", "rope_cache.hip", "attn_f32.hip", "attn_bf16.hip", "mfma_peak.hip"]
 
 # packed fp32 instructions are kept off for all device code on the test machines
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

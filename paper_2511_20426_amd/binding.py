@@ -28,6 +28,7 @@ EXPORTS = (
     "kv_cache_evict", "kv_cache_retag", "kv_cache_snapshot", "kv_cache_page_index",
     "rope3d_apply", "cascade_attn_forward", "ca_debug_visibility", "ca_set_kernel_variant",
     "ca_strerror", "ca_last_device_error",
+    "ca_mfma_microbench",
     "ca_sched_create", "ca_sched_destroy", "ca_sched_batch", "ca_sched_advance", "ca_sched_state",
 )
 
@@ -96,6 +97,8 @@ def _load() -> C.CDLL:
                                         C.POINTER(i64), i32, C.POINTER(i32)]
     lib.ca_set_kernel_variant.restype = i32
     lib.ca_set_kernel_variant.argtypes = [vp, i32]
+    lib.ca_mfma_microbench.restype = i32
+    lib.ca_mfma_microbench.argtypes = [i32, i32, vp, C.c_size_t, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.ca_sched_create.restype = i32
     lib.ca_sched_create.argtypes = [i64, i32, C.POINTER(i32), i32, C.POINTER(vp)]
     lib.ca_sched_destroy.restype = i32
@@ -229,6 +232,14 @@ class Context:
 
     def set_kernel_variant(self, variant: int) -> None:
         _check(lib.ca_set_kernel_variant(self._h, variant), "ca_set_kernel_variant")
+
+
+def mfma_microbench(data_kind: int, trips: int, scratch_ptr: int, scratch_bytes: int, stream: int = 0):
+    """(TFLOP/s, shader clock in GHz) of an MFMA-only loop on every CU."""
+    t, c = C.c_double(0.0), C.c_double(0.0)
+    _check(lib.ca_mfma_microbench(data_kind, trips, scratch_ptr, scratch_bytes, stream, C.byref(t), C.byref(c)),
+           "ca_mfma_microbench")
+    return t.value, c.value
 
 
 class Scheduler:

@@ -180,6 +180,12 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
   return CA_OK;
 }
 
+int32_t ca_mfma_microbench(int32_t data_kind, int32_t trips, void* scratch_dev, size_t scratch_bytes,
+                           void* hip_stream, double* tflops, double* clock_ghz) {
+  if ((data_kind != 0 && data_kind != 1) || trips < 1 || trips > (1 << 24) || !scratch_dev) return CA_EINVAL;
+  return ca::run_mfma_microbench(data_kind, trips, scratch_dev, scratch_bytes, hip_stream, tflops, clock_ghz);
+}
+
 int32_t ca_set_kernel_variant(ca_ctx* ctx, int32_t variant) {
   if (!ctx) return CA_EINVAL;
   if (int32_t rc = ca::attn_bf16_variant_ok(variant)) return rc;

@@ -96,6 +96,8 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
 int32_t attn_bf16_variant_ok(int variant);
 
 // Launchers end with this: CA_OK, or CA_EDEVICE after recording the HIP error text.
+int32_t run_mfma_microbench(int data_kind, int trips, void* scratch, size_t scratch_bytes, void* stream,
+                            double* tflops, double* clock_ghz);
 int32_t finish_launch(const char* what);
 const char* last_device_error();
 

@@ -56,7 +56,10 @@ import sys
 # then meaningless; the shipped library is always built with 0.
 ABL = int(os.environ.get("CA_ABL", "0"))
 
-D_AHEAD = 5          # operand fragments are read this many MFMA pairs ahead of use
+# Schedule parameters can be overridden for tuning runs: CA_TUNE="cap=8.2,d_ahead=4,kbar=8,kr2=3,espread=24"
+TUNE = dict(kv.split("=") for kv in os.environ.get("CA_TUNE", "").split(",") if kv)
+
+D_AHEAD = int(TUNE.get("d_ahead", 5))          # operand fragments are read this many MFMA pairs ahead of use
 PAGE = 32768
 VRING = 65536
 
@@ -297,7 +300,7 @@ def p_word(p_base, j):
 # is not taken 2.5 (5 if it directly follows the instruction that sets its condition), everything
 # else (VALU, SALU, s_waitcnt, s_nop) 1.  Whatever exceeds 8 quanta between two MFMAs delays the
 # second one by the full excess; there is no carry-over of slack between slots.
-CAP = 8.0
+CAP = float(TUNE.get("cap", 8.2))
 
 
 def quanta(line):
@@ -363,9 +366,10 @@ def schedule(fixed_load, atoms):
     return placed
 
 
+E_SPREAD = int(TUNE.get("espread", 22))    # the 32 exponentials of a step are due by this slot
 THRESH = "0x47800000"     # 2^16: a step's row sum of 16 probabilities above this moves the reference
-K_BARRIER_SLOT = 16       # step 2: K(q+1) visible, slot of K(q) free
-N_KLOADS_R2 = 2           # of the 8 loads of K(q+2), how many issue in step 2 (the rest in step 3)
+K_BARRIER_SLOT = int(TUNE.get("kbar", 16))       # step 2: K(q+1) visible, slot of K(q) free
+N_KLOADS_R2 = int(TUNE.get("kr2", 2))           # of the 8 loads of K(q+2), how many issue in step 2 (the rest in step 3)
 
 
 def build_step(R, par):
@@ -401,12 +405,12 @@ def build_step(R, par):
         # row sums of the previous step join the running sums; this step's start afresh
         lacc = [Atom([f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(TS[nt])}"], 0, 0, hard=1) for nt in range(2)]
         atoms += lacc
-        exps = [Atom([f"v_exp_f32 {V(PX + e)}, {V(s_cur + e)}"], 0, (e * 22) // 32, hard=26) for e in range(32)]
+        exps = [Atom([f"v_exp_f32 {V(PX + e)}, {V(s_cur + e)}"], 0, (e * E_SPREAD) // 32, hard=min(E_SPREAD + 4, 27)) for e in range(32)]
         atoms += exps
         last_sum = [None, None]
         for j in range(1, 32, 2):
             nt = j >> 4
-            deps, dl = [exps[j - 1], exps[j]], (j * 22) // 32 + 5
+            deps, dl = [exps[j - 1], exps[j]], (j * E_SPREAD) // 32 + 5
             atoms.append(Atom([f"v_cvt_pk_bf16_f32 {V(p_word(p_cur, j))}, {V(PX + j - 1)}, {V(PX + j)}"],
                               0, dl, deps, 2, hard=29))
             if last_sum[nt] is None:

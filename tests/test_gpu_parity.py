@@ -434,3 +434,22 @@ def test_algorithm1_rollout_driver(mode):
         assert [s.astuple() for s in pool.ctx.kv_cache_snapshot()] == cache.snapshot()
     assert ro.step() is None
     assert [r.emitted for r in ro.records if r.emitted >= 0] == list(range(n_blocks))
+
+
+def test_mfma_microbench_reports_a_plausible_ceiling():
+    """The MFMA-only loop: below the nominal peak, above half of it, clock within the chip's range;
+    zero operands switch less and must not be slower than random ones."""
+    import torch
+    from paper_2511_20426_amd import binding as B
+    probe = torch.empty(1 << 16, dtype=torch.uint8, device="cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    rnd = B.mfma_microbench(1, 20000, probe.data_ptr(), probe.numel(), stream)
+    zer = B.mfma_microbench(0, 20000, probe.data_ptr(), probe.numel(), stream)
+    _say(f"mfma only: random {rnd[0]:.0f} TFLOP/s at {rnd[1]:.2f} GHz, zeros {zer[0]:.0f} TFLOP/s at {zer[1]:.2f} GHz")
+    for t, c in (rnd, zer):
+        assert 1000.0 < t < 2600.0 and 1.0 < c < 2.6
+    assert zer[0] > 0.95 * rnd[0]
+    with pytest.raises(B.CascadeAttnError):
+        B.mfma_microbench(2, 10, probe.data_ptr(), probe.numel(), stream)
+    with pytest.raises(B.CascadeAttnError):
+        B.mfma_microbench(1, 10, probe.data_ptr(), 8, stream)
