@@ -19,7 +19,7 @@
 //                   key order the accumulator hands over, so no data movement is needed
 //                   between the two products (see cascade_attn.h for the page format).
 //   Softmax is the running-reference form in base 2: p = exp2(s*c - m_ref), c = log2(e)/sqrt(D);
-//   m_ref moves (and the accumulators are rescaled) only when a score exceeds it by 2^8.
+//   m_ref moves (and the accumulators are rescaled) only when the probabilities of a step sum past 2^16.
 //   The 256-byte page rows are stored with their 16-byte chunks XOR-swizzled by (row & 15),
 //   which makes every ds_read_b128 of an MFMA operand bank-conflict free.
 //   Workgroups are numbered so that the eight XCDs each take a contiguous range of
