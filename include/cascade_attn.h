@@ -156,6 +156,17 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
  * workgroup walks its whole KV range).  Unknown values are rejected with CA_EINVAL. */
 int32_t ca_set_kernel_variant(ca_ctx* ctx, int32_t variant);
 
+/* ---- The linear maps either side of the attention inside a layer (QKV projection before it,
+ * output projection after it): y[m][n] = sum_k x[m][k] * w[n][k], bf16 in and out, fp32
+ * accumulation, one rounding to nearest even at the end.  All three matrices are device memory,
+ * row-major with row strides ldx, ldw, ldy in elements (multiples of 8, 16-byte aligned bases);
+ * nothing is allocated and nothing but y[0..m_rows) x [0..n_out) is written.  The QKV projection
+ * writes [tokens][3][heads][head_dim] rows that rope3d_apply and kv_cache_append take as strided
+ * views.  Supported shapes: n_out a multiple of 256, k_in a multiple of 128 (CA_EUNSUPPORTED
+ * otherwise); m_rows is free. */
+int32_t layer_linear_bf16(const void* x_dev, const void* w_dev, void* y_dev, int64_t m_rows, int32_t n_out,
+                          int32_t k_in, int64_t ldx, int64_t ldw, int64_t ldy, void* hip_stream);
+
 /* Measurement aid, not a step of the method: runs v_mfma_f32_32x32x16_bf16 back to back on every
  * CU (nothing else in the loop) and reports the sustained dense bf16 rate and the shader clock the
  * chip held meanwhile -- the practical ceiling to read cascade_attn_forward's TFLOP/s against.

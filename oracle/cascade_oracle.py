@@ -285,3 +285,13 @@ def algorithm1_trace(n_blocks: int, n_gpus: int, n_timesteps: int = 5):
             d = min(d + 1, n_gpus - 1)
             tau += 1
     return trace
+
+
+def layer_linear(x: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """The linear maps either side of the attention inside a layer (QKV projection, output
+    projection): y[m, n] = sum_k x[m, k] w[n, k], weights stored [out, in].  fp64; the paper
+    treats these as part of the generator G_theta (Sec. 3.1) and gives no more than that."""
+    x = np.asarray(x, dtype=np.float64)
+    w = np.asarray(w, dtype=np.float64)
+    assert x.ndim == 2 and w.ndim == 2 and x.shape[1] == w.shape[1]
+    return x @ w.T

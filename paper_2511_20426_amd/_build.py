@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.environ.get("CASCADE_ATTN_LIB") or os.path.join(PKG, "libcascade_attn.so")
 
-SOURCES = ["ca_meta.cpp", "ca_api.cpp", "ca_sched.cpp", "rope_cache.hip", "attn_f32.hip", "attn_bf16.hip", "mfma_peak.hip"]
+SOURCES = ["ca_meta.cpp", "ca_api.cpp", "ca_sched.cpp", "rope_cache.hip", "attn_f32.hip", "attn_bf16.hip", "mfma_peak.hip", "gemm_bf16.hip"]
 
 # packed fp32 instructions are kept off for all device code on the test machines
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
@@ -24,13 +24,16 @@ def hipcc() -> str:
     return exe
 
 
-def build(verbose: bool = False, extra=()) -> str:
+def build(verbose: bool = False, extra=(), bdir: str | None = None) -> str:
     objs = []
-    bdir = os.path.join(PKG, "_build")
+    bdir = bdir or os.path.join(PKG, "_build")
     os.makedirs(bdir, exist_ok=True)
     # the hand-scheduled attention main loop is emitted as an inline-assembly include
     subprocess.run([sys.executable, os.path.join(CSRC, "gen_attn_core.py"),
                     os.path.join(bdir, "attn_core_gfx950.inc")], check=True,
+                   stdout=None if verbose else subprocess.DEVNULL)
+    subprocess.run([sys.executable, os.path.join(CSRC, "gen_gemm_core.py"),
+                    os.path.join(bdir, "gemm_core_gfx950.inc")], check=True,
                    stdout=None if verbose else subprocess.DEVNULL)
     common = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-I", os.path.join(ROOT, "include"),
               "-I", CSRC, "-I", bdir, "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"] + DEVICE_FLAGS + list(extra)

@@ -28,7 +28,7 @@ EXPORTS = (
     "kv_cache_evict", "kv_cache_retag", "kv_cache_snapshot", "kv_cache_page_index",
     "rope3d_apply", "cascade_attn_forward", "ca_debug_visibility", "ca_set_kernel_variant",
     "ca_strerror", "ca_last_device_error",
-    "ca_mfma_microbench",
+    "ca_mfma_microbench", "layer_linear_bf16",
     "ca_sched_create", "ca_sched_destroy", "ca_sched_batch", "ca_sched_advance", "ca_sched_state",
 )
 
@@ -99,6 +99,8 @@ def _load() -> C.CDLL:
     lib.ca_set_kernel_variant.argtypes = [vp, i32]
     lib.ca_mfma_microbench.restype = i32
     lib.ca_mfma_microbench.argtypes = [i32, i32, vp, C.c_size_t, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.layer_linear_bf16.restype = i32
+    lib.layer_linear_bf16.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, i64, vp]
     lib.ca_sched_create.restype = i32
     lib.ca_sched_create.argtypes = [i64, i32, C.POINTER(i32), i32, C.POINTER(vp)]
     lib.ca_sched_destroy.restype = i32
@@ -232,6 +234,11 @@ class Context:
 
     def set_kernel_variant(self, variant: int) -> None:
         _check(lib.ca_set_kernel_variant(self._h, variant), "ca_set_kernel_variant")
+
+
+def layer_linear_bf16(x_ptr: int, w_ptr: int, y_ptr: int, m_rows: int, n_out: int, k_in: int,
+                      ldx: int, ldw: int, ldy: int, stream: int = 0) -> None:
+    _check(lib.layer_linear_bf16(x_ptr, w_ptr, y_ptr, m_rows, n_out, k_in, ldx, ldw, ldy, stream), "layer_linear_bf16")
 
 
 def mfma_microbench(data_kind: int, trips: int, scratch_ptr: int, scratch_bytes: int, stream: int = 0):

@@ -180,6 +180,14 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
   return CA_OK;
 }
 
+int32_t layer_linear_bf16(const void* x_dev, const void* w_dev, void* y_dev, int64_t m_rows, int32_t n_out,
+                          int32_t k_in, int64_t ldx, int64_t ldw, int64_t ldy, void* hip_stream) {
+  if (!x_dev || !w_dev || !y_dev) return CA_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(x_dev) | reinterpret_cast<uintptr_t>(w_dev) | reinterpret_cast<uintptr_t>(y_dev)) & 15)
+    return CA_EINVAL;
+  return ca::launch_gemm_bf16(x_dev, w_dev, y_dev, m_rows, n_out, k_in, ldx, ldw, ldy, hip_stream);
+}
+
 int32_t ca_mfma_microbench(int32_t data_kind, int32_t trips, void* scratch_dev, size_t scratch_bytes,
                            void* hip_stream, double* tflops, double* clock_ghz) {
   if ((data_kind != 0 && data_kind != 1) || trips < 1 || trips > (1 << 24) || !scratch_dev) return CA_EINVAL;

@@ -98,6 +98,8 @@ int32_t attn_bf16_variant_ok(int variant);
 // Launchers end with this: CA_OK, or CA_EDEVICE after recording the HIP error text.
 int32_t run_mfma_microbench(int data_kind, int trips, void* scratch, size_t scratch_bytes, void* stream,
                             double* tflops, double* clock_ghz);
+int32_t launch_gemm_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
+                         int64_t ldx, int64_t ldw, int64_t ldy, void* stream);
 int32_t finish_launch(const char* what);
 const char* last_device_error();
 

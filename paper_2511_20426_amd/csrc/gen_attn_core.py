@@ -51,6 +51,9 @@ from __future__ import annotations
 import os
 import sys
 
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from issue_sched import Atom, quanta, schedule  # noqa: E402
+
 # Timing experiments only (CA_ABL in the environment of the build): switch parts of the loop off.
 # 1 no softmax arithmetic, 2 no LDS operand reads, 4 no page loads, 8 no barriers.  Results are
 # then meaningless; the shipped library is always built with 0.
@@ -293,77 +296,8 @@ def p_word(p_base, j):
 
 
 # ---------------------------------------------------------------------------- issue-slot scheduling
-# Measured on gfx950 with one wave per SIMD: the wave issues one instruction per 4 cycles
-# whatever its kind; an MFMA 32x32x16 holds the issue port for 8 cycles and the matrix pipe for
-# 32, so the 32 cycles from one MFMA to the next have room for 6 more issue quanta of 4 cycles.
-# v_exp_f32 takes 2 quanta, ds_read_b128 2.2, v_readlane 2, a global->LDS load 2.7, a branch that
-# is not taken 2.5 (5 if it directly follows the instruction that sets its condition), everything
-# else (VALU, SALU, s_waitcnt, s_nop) 1.  Whatever exceeds 8 quanta between two MFMAs delays the
-# second one by the full excess; there is no carry-over of slack between slots.
+# (model and scheduler: issue_sched.py)
 CAP = float(TUNE.get("cap", 8.2))
-
-
-def quanta(line):
-    op = line.split()[0]
-    if op.endswith(":") or op.startswith(";"):
-        return 0.0
-    if op.startswith("v_mfma"):
-        return 2.0
-    if op.startswith("v_exp"):
-        return 2.0
-    if op.startswith("ds_read_b128"):
-        return 2.2
-    if op.startswith("v_readlane"):
-        return 2.0
-    if op.startswith("global_load"):
-        return 2.7
-    if op.startswith("s_cbranch"):
-        return 2.5
-    return 1.0
-
-
-class Atom:
-    """Instructions that stay together, with the earliest slot they may issue in (`ready`, or
-    `gap` slots after the latest of the atoms in `after`) and the slot they should issue by."""
-    def __init__(self, lines, ready=0, deadline=31, after=(), gap=0, tag=None, hard=31):
-        self.lines = list(lines)
-        self.cost = sum(quanta(l) for l in self.lines)
-        self.ready, self.deadline, self.tag, self.hard = ready, deadline, tag, hard
-        self.after = [(a, gap) for a in after]            # (atom, slots that must lie between)
-        self.slot = None
-
-    def ready_slot(self):
-        r = self.ready
-        for a, gap in self.after:
-            if a.slot is None:
-                return None
-            r = max(r, a.slot + gap)
-        return r
-
-
-def schedule(fixed_load, atoms):
-    """Earliest-deadline-first list scheduling of `atoms` into the 32 slots of a step.
-    fixed_load[i]: quanta already spoken for in slot i.  Returns per-slot lists of atoms."""
-    placed = [[] for _ in range(32)]
-    pending = list(atoms)
-    for i in range(32):
-        cap = CAP - fixed_load[i]
-        while True:
-            cands = [a for a in pending if a.ready_slot() is not None and a.ready_slot() <= i]
-            cands.sort(key=lambda a: a.deadline)
-            pick = None
-            for a in cands:
-                if a.cost <= cap + 1e-9 or a.hard <= i:
-                    pick = a
-                    break
-            if pick is None:
-                break
-            pick.slot = i
-            placed[i].append(pick)
-            pending.remove(pick)
-            cap -= pick.cost
-    assert not pending, [a.lines for a in pending]
-    return placed
 
 
 E_SPREAD = int(TUNE.get("espread", 22))    # the 32 exponentials of a step are due by this slot
@@ -463,7 +397,7 @@ def build_step(R, par):
     atoms += loads
 
     fixed = [2.0 + sum(quanta(l) for l in head[i] + tail[i]) for i in range(32)]
-    placed = schedule(fixed, atoms)
+    placed = schedule(fixed, atoms, CAP)
     for i in (30, 31):
         for a in placed[i]:
             assert not any(l.split()[0].startswith(("s_add", "s_sub", "s_cmp", "s_and", "s_mul")) for l in a.lines), a.lines

@@ -77,3 +77,15 @@ class CascadePool:
         assert o.is_contiguous()
         self.ctx.cascade_attn_forward(q_rot.data_ptr(), list(inflight), mode, o.data_ptr(), self._stream())
         return o
+
+
+def linear(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """y = x @ w.T through layer_linear_bf16: x [M, K], w [N, K], y [M, N], bf16, rows may be
+    strided (last dimension contiguous)."""
+    assert x.is_cuda and w.is_cuda and x.dtype == torch.bfloat16 and w.dtype == torch.bfloat16
+    assert x.dim() == 2 and w.dim() == 2 and x.shape[1] == w.shape[1] and x.stride(1) == 1 and w.stride(1) == 1
+    y = torch.empty((x.shape[0], w.shape[0]), dtype=torch.bfloat16, device=x.device) if out is None else out
+    assert y.shape == (x.shape[0], w.shape[0]) and y.stride(1) == 1 and y.dtype == torch.bfloat16
+    B.layer_linear_bf16(x.data_ptr(), w.data_ptr(), y.data_ptr(), x.shape[0], w.shape[0], x.shape[1],
+                        x.stride(0), w.stride(0), y.stride(0), torch.cuda.current_stream(x.device).cuda_stream)
+    return y

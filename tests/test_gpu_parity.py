@@ -453,3 +453,68 @@ def test_mfma_microbench_reports_a_plausible_ceiling():
         B.mfma_microbench(2, 10, probe.data_ptr(), probe.numel(), stream)
     with pytest.raises(B.CascadeAttnError):
         B.mfma_microbench(1, 10, probe.data_ptr(), 8, stream)
+
+
+# --------------------------------------------------------------------------- layer_linear_bf16
+
+def _linear_check(got, x, w, rows, what):
+    """bf16 result of an fp32-accumulated dot product against the fp64 oracle: one rounding to
+    bf16 (half an ulp = 2^-9 relative; 2^-8 allowed) plus the accumulation error, bounded by a few
+    2^-24 of sum_k |x||w| per addition level (1e-5 of that sum allowed)."""
+    xf, wf = W.to_f64(x[rows]), W.to_f64(w)
+    ref = orc.layer_linear(xf, wf)
+    bound = np.abs(ref) * 2.0 ** -8 + 1e-5 * orc.layer_linear(np.abs(xf), np.abs(wf)) + 1e-30
+    err = np.abs(got[rows].astype(np.float64) - ref)
+    worst = float((err / bound).max())
+    _say(f"[parity] {what}: max err/bound = {worst:.3f}, rel L2 = {Hn.rel_l2(got[rows], ref):.2e}")
+    assert worst <= 1.0, what
+
+
+@pytest.mark.parametrize("M,N,K,pad", [(300, 256, 128, 0), (1000, 512, 384, 8), (257, 768, 1024, 24), (1, 256, 128, 0)])
+def test_layer_linear_small_full(M, N, K, pad):
+    """Every output element; M not a multiple of the 256-row tile, K of several loop trips,
+    row strides larger than the row (pad) for all three matrices."""
+    import torch
+    from paper_2511_20426_amd.runner import linear
+    x, w = W.draw_linear(M, N, K, seed=41)
+    xt = torch.zeros((M, K + pad), dtype=torch.bfloat16, device="cuda:0")
+    wt = torch.zeros((N, K + pad), dtype=torch.bfloat16, device="cuda:0")
+    xt[:, :K] = Hn.to_torch(x, "bf16"); wt[:, :K] = Hn.to_torch(w, "bf16")
+    yt = torch.full((M + 3, N + pad), 7.0, dtype=torch.bfloat16, device="cuda:0")
+    _say(f"linear M={M} N={N} K={K} pad={pad}")
+    linear(xt[:, :K], wt[:, :K], out=yt[:M, :N])
+    torch.cuda.synchronize()
+    got = Hn.from_torch(yt, "bf16")
+    assert (got[M:] == 7.0).all() and (got[:, N:] == 7.0).all()          # nothing outside y is written
+    _linear_check(got[:M, :N], x, w, np.arange(M), f"linear {M}x{N}x{K}")
+
+
+def test_layer_linear_qkv_and_output_projection_shapes_sampled():
+    """The two projections of a Wan-14B layer for five blocks in flight (23400 tokens, model
+    width 5120): QKV 5120 -> 15360 and output 5120 -> 5120, checked on sampled rows x all columns."""
+    import torch
+    from paper_2511_20426_amd.runner import linear
+    M, K = 23400, 5120
+    rows = np.unique(np.concatenate([W.sample_rows(M, 24, seed=5, tile_edges=(256,))[:40], [M - 257, M - 256, M - 1]]))
+    for N in (15360, 5120):
+        x, w = W.draw_linear(M, N, K, seed=43)
+        _say(f"linear M={M} N={N} K={K} sampled rows={len(rows)}")
+        y = linear(Hn.to_torch(x, "bf16"), Hn.to_torch(w, "bf16"))
+        torch.cuda.synchronize()
+        got = Hn.from_torch(y, "bf16")
+        _linear_check(got, x, w, rows, f"linear {M}x{N}x{K}")
+
+
+def test_layer_linear_rejects_unsupported_shapes():
+    import torch
+    from paper_2511_20426_amd import binding as B
+    t = torch.zeros((512, 512), dtype=torch.bfloat16, device="cuda:0")
+    p = t.data_ptr()
+    for args, code in (((p, p, p, 256, 200, 128, 512, 512, 512), B.CA_EUNSUPPORTED),   # n_out not a multiple of 256
+                       ((p, p, p, 256, 256, 96, 512, 512, 512), B.CA_EUNSUPPORTED),    # k_in not a multiple of 128
+                       ((p, p, p, 256, 256, 128, 64, 512, 512), B.CA_EINVAL),          # row stride shorter than the row
+                       ((p, p, p + 2, 256, 256, 128, 512, 512, 512), B.CA_EINVAL),     # misaligned
+                       ((0, p, p, 256, 256, 128, 512, 512, 512), B.CA_EINVAL)):
+        with pytest.raises(B.CascadeAttnError) as e:
+            B.layer_linear_bf16(*args)
+        assert e.value.code == code, args

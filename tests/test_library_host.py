@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "cascade_attn.h")).read()
     body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(\w+)\s*\(", body)) - {"defined", "ceil"}
-    declared = {d for d in declared if d.startswith(("ca_", "kv_cache_", "rope3d_", "cascade_"))}
+    declared = {d for d in declared if d.startswith(("ca_", "kv_cache_", "rope3d_", "cascade_", "layer_"))}
     assert declared == set(B.EXPORTS), declared ^ set(B.EXPORTS)
     lib = ctypes.CDLL(B.LIB_PATH)
     for name in declared:

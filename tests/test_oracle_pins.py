@@ -451,3 +451,23 @@ def test_schedule_matches_algorithm1_trace():
         b, batch = orc.cascade_schedule(step, T, 5)
         assert b == tr[step][0]
         assert batch == [(g, T[ti]) for g, ti in tr[step][3]]
+
+
+def test_layer_linear_against_the_definition_and_special_cases():
+    """x @ w.T: brute force over every (m, n, k) on a tiny case, identity and one-hot weights
+    (which pick columns of x), and linearity in each argument."""
+    rng = np.random.default_rng(3)
+    x, w = rng.standard_normal((5, 7)), rng.standard_normal((4, 7))
+    brute = np.zeros((5, 4))
+    for m in range(5):
+        for n in range(4):
+            for k in range(7):
+                brute[m, n] += x[m, k] * w[n, k]
+    np.testing.assert_allclose(orc.layer_linear(x, w), brute, rtol=1e-13, atol=1e-13)
+    np.testing.assert_array_equal(orc.layer_linear(x, np.eye(7)), x)
+    onehot = np.zeros((2, 7)); onehot[0, 3] = 1.0; onehot[1, 6] = -2.0
+    np.testing.assert_array_equal(orc.layer_linear(x, onehot), np.stack([x[:, 3], -2.0 * x[:, 6]], axis=1))
+    x2, w2 = rng.standard_normal((5, 7)), rng.standard_normal((4, 7))
+    np.testing.assert_allclose(orc.layer_linear(x + 2 * x2, w), orc.layer_linear(x, w) + 2 * orc.layer_linear(x2, w), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(orc.layer_linear(x, w - w2), orc.layer_linear(x, w) - orc.layer_linear(x, w2), rtol=1e-12, atol=1e-12)
+    assert orc.layer_linear(x, w).shape == (5, 4)            # [rows, out], weights stored [out, in]

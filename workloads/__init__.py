@@ -193,3 +193,12 @@ def sample_rows(L: int, n_random: int, seed: int, tile_edges=(128, 256)) -> np.n
     rng = np.random.default_rng(seed)
     rows.update(int(r) for r in rng.integers(0, L, size=n_random))
     return np.array(sorted(r for r in rows if 0 <= r < L), dtype=np.int64)
+
+
+def draw_linear(m_rows: int, n_out: int, k_in: int, seed: int, x_scale: float = 1.0):
+    """Activations X [m_rows, k_in] ~ N(0,1) * x_scale and weights W [n_out, k_in] ~ N(0,1) / sqrt(k_in)
+    (outputs of unit scale, as after a normalised layer input), both rounded to bf16 bit patterns."""
+    rng = np.random.default_rng([seed, m_rows, n_out, k_in])
+    x = rng.standard_normal((m_rows, k_in), dtype=np.float32) * np.float32(x_scale)
+    w = rng.standard_normal((n_out, k_in), dtype=np.float32) * np.float32(1.0 / np.sqrt(k_in))
+    return store(x, "bf16"), store(w, "bf16")
