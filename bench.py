@@ -72,6 +72,63 @@ def cpu_baseline(w, seconds_target=15.0):
     }
 
 
+# The projections either side of the attention at the Wan-14B width for five blocks in flight
+# (not part of the default step: --workload linear_qkv_14b / linear_out_14b)
+LINEAR_WORKLOADS = {"linear_qkv_14b": (23400, 15360, 5120), "linear_out_14b": (23400, 5120, 5120)}
+
+
+def bench_linear(args, torch, W, B) -> int:
+    from paper_2511_20426_amd.runner import linear
+    import numpy as np
+    M, N, K = LINEAR_WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev).manual_seed(0)
+    x = torch.randn((M, K), generator=gen, device=dev).to(torch.bfloat16)
+    wt = (torch.randn((N, K), generator=gen, device=dev) / K ** 0.5).to(torch.bfloat16)
+    y = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    for _ in range(args.warmup):
+        linear(x, wt, out=y)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        linear(x, wt, out=y)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    kms = e0.elapsed_time(e1) / args.steps
+    flops = 2.0 * M * N * K
+    result = {
+        "metric": "bf16 linear (y = x w^T) TFLOP/s, Wan-14B width, 5 blocks of tokens", "value": flops / ms / 1e9,
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "m_rows": M, "n_out": N, "k_in": K, "flops_per_step": flops},
+        "roofline": {"bound": "mfma", "kernel": "gemm_bf16_kernel", "achieved": flops / kms / 1e9,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": flops / kms / 1e9 / PEAK_BF16_TFLOPS,
+                     "avg_launch_ms": kms, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import cascade_oracle as orc
+        rows = 512
+        xs = W.to_f64(W.f32_to_bf16_bits(x[:rows].float().cpu().numpy()))
+        ws = W.to_f64(W.f32_to_bf16_bits(wt.float().cpu().numpy()))
+        t0, n = time.perf_counter(), 0
+        while time.perf_counter() - t0 < 10.0:
+            orc.layer_linear(xs, ws)
+            n += 1
+        dt = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        result["cpu_baseline"] = {"value": 2.0 * rows * N * K * n / dt / 1e12, "unit": "TFLOP/s", "cores": int(cores),
+                                  "kind": "oracle", "sample": f"fp64 numpy oracle on the first {rows} rows, {n} passes in {dt:.1f} s"}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +167,8 @@ def main() -> int:
         torch.cuda.synchronize()
         print(json.dumps({"copy_bytes_read": x.numel() * 2, "copy_bytes_written": x.numel() * 2}))
         return 0
+    if args.workload in LINEAR_WORKLOADS:
+        return bench_linear(args, torch, W, B)
     w = W.CONFIGS[args.workload]
     if args.inflight is not None or args.cached is not None:
         from dataclasses import replace
