@@ -45,8 +45,13 @@ class CascadeRollout:
     pool: CascadePool
     n_blocks: int
     timesteps: Sequence[int]
-    qkv_fn: Callable
+    qkv_fn: Optional[Callable] = None
     out_fn: Optional[Callable] = None
+    # optional stand-ins for the layer around the attention, run inside the timed region:
+    # batch_qkv_fn(batch) -> [(q, k, v) per block] (e.g. one QKV projection for the whole batch),
+    # post_fn(o) (e.g. the output projection)
+    batch_qkv_fn: Optional[Callable] = None
+    post_fn: Optional[Callable] = None
     mode: int = B.CA_BIDIRECTIONAL
     window_blocks: Optional[int] = None        # clean blocks kept; default: the pool's window
     epoch: int = 0
@@ -78,9 +83,12 @@ class CascadeRollout:
         it = self.sched.state()[3]
         if self.timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        staged = [self.qkv_fn(g, ti, it, i) for i, (g, ti, _) in enumerate(batch)]
+        if self.batch_qkv_fn is None:
+            staged = [self.qkv_fn(g, ti, it, i) for i, (g, ti, _) in enumerate(batch)]
         if self.timed:
             e0.record()
+        if self.batch_qkv_fn is not None:
+            staged = self.batch_qkv_fn(batch)
         n = len(batch)
         for i, ((g, ti, t), (q, k, v)) in enumerate(zip(batch, staged)):
             pool.append(g, t, self.epoch, k, v)
@@ -88,6 +96,8 @@ class CascadeRollout:
         infl = [g for g, _, _ in batch]
         qr = pool.rope(self._q[:n * L], pool.frames_per_block * infl[0], out=self._qr[:n * L])
         o = pool.forward(qr, infl, self.mode, out=self._o[:n * L])
+        if self.post_fn is not None:
+            self.post_fn(o)
         emitted, completed = self.sched.advance()
         evicted = -1
         if completed >= 0:
@@ -138,6 +148,8 @@ def main(argv=None) -> None:
                          "of the paper's accounting, 5 in flight + 2 cached)")
     ap.add_argument("--mode", choices=("bidirectional", "block_causal"), default="bidirectional")
     ap.add_argument("--repeats", type=int, default=3)
+    ap.add_argument("--layer", action="store_true",
+                    help="include the QKV and output projections (synthetic weights) in every iteration")
     a = ap.parse_args(argv)
     w = W.CONFIGS[a.workload]
     dev = torch.device("cuda:0")
@@ -150,10 +162,31 @@ def main(argv=None) -> None:
     bank = [tuple((torch.randn((L, H, D), generator=gen, device=dev) * w.input_scale).to(torch.bfloat16)
                   for _ in range(3)) for _ in range(len(W.TIMESTEPS))]
     mode = B.CA_BIDIRECTIONAL if a.mode == "bidirectional" else B.CA_BLOCK_CAUSAL
+    hooks = {}
+    if a.layer:
+        from .runner import linear
+        width = H * D
+        x = (torch.randn((len(W.TIMESTEPS) * L, width), generator=gen, device=dev)).to(torch.bfloat16)
+        w_qkv = (torch.randn((3 * width, width), generator=gen, device=dev) / width ** 0.5).to(torch.bfloat16)
+        w_out = (torch.randn((width, width), generator=gen, device=dev) / width ** 0.5).to(torch.bfloat16)
+        qkv = torch.empty((len(W.TIMESTEPS) * L, 3, H, D), dtype=torch.bfloat16, device=dev)
+        y = torch.empty((len(W.TIMESTEPS) * L, width), dtype=torch.bfloat16, device=dev)
+
+        def batch_qkv_fn(batch):
+            n = len(batch) * L
+            linear(x[:n], w_qkv, out=qkv[:n].view(n, 3 * width))
+            return [(qkv[i * L:(i + 1) * L, 0], qkv[i * L:(i + 1) * L, 1], qkv[i * L:(i + 1) * L, 2])
+                    for i in range(len(batch))]
+
+        def post_fn(o):
+            n = o.shape[0]
+            linear(o.view(n, width), w_out, out=y[:n])
+
+        hooks = dict(batch_qkv_fn=batch_qkv_fn, post_fn=post_fn)
     rates, steady_ms = [], []
     for rep in range(a.repeats + 1):                      # first pass warms up
         pool = CascadePool.for_workload(pool_w)
-        ro = CascadeRollout(pool, a.blocks, W.TIMESTEPS, lambda g, ti, it, i: bank[i], mode=mode, timed=True)
+        ro = CascadeRollout(pool, a.blocks, W.TIMESTEPS, lambda g, ti, it, i: bank[i], mode=mode, timed=True, **hooks)
         recs = ro.run()
         if rep:
             rates.append(streaming_rate(recs))
@@ -162,7 +195,8 @@ def main(argv=None) -> None:
     window = pool_w.window_blocks
     print(json.dumps({
         "metric": "steady_state_cascade_iterations_per_s", "value": sum(rates) / len(rates),
-        "unit": "iterations/s (one attention layer; one block of 3 latent frames emitted per iteration)",
+        "unit": "iterations/s (one attention layer%s; one block of 3 latent frames emitted per iteration)"
+                % (" with its QKV and output projections" if a.layer else ""),
         "protocol": "mean over the iterations emitting the 8th and 9th block of a %d-block rollout" % a.blocks,
         "workload": w.name, "mode": a.mode, "clean_window_blocks": window,
         "iteration_ms": steady_ms, "iterations": len(recs), "data": "synthetic",

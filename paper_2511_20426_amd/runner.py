@@ -89,3 +89,24 @@ def linear(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) ->
     B.layer_linear_bf16(x.data_ptr(), w.data_ptr(), y.data_ptr(), x.shape[0], w.shape[0], x.shape[1],
                         x.stride(0), w.stride(0), y.stride(0), torch.cuda.current_stream(x.device).cuda_stream)
     return y
+
+
+def attention_layer(pool: CascadePool, x: torch.Tensor, w_qkv: torch.Tensor, w_out: torch.Tensor,
+                    inflight: Sequence[int], timesteps: Sequence[int], epoch: int, mode: int) -> torch.Tensor:
+    """One self-attention layer around the shared pool, for the blocks in flight (oldest first,
+    consecutive in the video): QKV projection, K/V of every block published to the cache, Q
+    rotated, cascaded attention, output projection.  x [C*L, width], w_qkv [3*width, width] with
+    output rows ordered (q|k|v, head, dim), w_out [width, width]; width = heads * head_dim.
+    Library calls only; the q/k/v handed on are strided views of the projection's output."""
+    L, H, D = pool.block_tokens, pool.heads, pool.head_dim
+    n = len(inflight) * L
+    assert x.shape == (n, H * D) and w_qkv.shape == (3 * H * D, H * D) and w_out.shape == (H * D, H * D)
+    qkv = linear(x, w_qkv).view(n, 3, H, D)
+    for i, (g, t) in enumerate(zip(inflight, timesteps)):
+        pool.append(g, t, epoch, qkv[i * L:(i + 1) * L, 1], qkv[i * L:(i + 1) * L, 2])
+    q_rot = torch.empty((n, H, D), dtype=x.dtype, device=x.device)
+    # rope3d_apply wants equal strides for input and output: rotate in place in the view, then pack
+    pool.rope(qkv[:, 0], pool.frames_per_block * inflight[0], out=qkv[:, 0])
+    q_rot.copy_(qkv[:, 0])
+    o = pool.forward(q_rot, inflight, mode)
+    return linear(o.view(n, H * D), w_out)

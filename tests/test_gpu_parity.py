@@ -518,3 +518,35 @@ def test_layer_linear_rejects_unsupported_shapes():
         with pytest.raises(B.CascadeAttnError) as e:
             B.layer_linear_bf16(*args)
         assert e.value.code == code, args
+
+
+@pytest.mark.parametrize("mode", [BI, CA])
+def test_attention_layer_pipeline(mode):
+    """QKV projection -> K/V published + Q rotated (strided views of the projection's output) ->
+    cascaded attention -> output projection, against the same chain in the oracle (fp64
+    throughout).  The HIP path rounds q, k, v and the attention output to bf16 on the way, each
+    2^-9 relative, so the bar is looser than for one stage: relative L2 1e-2 (measured 4.6e-3)."""
+    import torch
+    from paper_2511_20426_amd.runner import CascadePool, attention_layer
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=6, grid_w=9, n_cached=1, n_inflight=2)
+    L, H, D = w.block_tokens, w.heads, w.head_dim
+    width = H * D
+    _say(f"attention layer pipeline: L={L} width={width} mode={mode}")
+    x_all, w_qkv = W.draw_linear(3 * L, 3 * width, width, seed=51)        # block 0 is cached, 1 and 2 in flight
+    _, w_out = W.draw_linear(1, width, width, seed=52)
+    pool = CascadePool.for_workload(w)
+    xt, wq, wo = (Hn.to_torch(a, "bf16") for a in (x_all, w_qkv, w_out))
+    attention_layer(pool, xt[:L], wq, wo, [0], [0], 0, BI)                # block 0 runs alone, becomes clean
+    pool.ctx.kv_cache_promote(0)
+    y = attention_layer(pool, xt[L:], wq, wo, [1, 2], [250, 500], 0, mode)
+    torch.cuda.synchronize()
+    got = Hn.from_torch(y, "bf16")
+    qkv = orc.layer_linear(W.to_f64(x_all), W.to_f64(w_qkv)).reshape(3 * L, 3, H, D)
+    pos = lambda g: orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w)
+    kb = [orc.rope3d(qkv[g * L:(g + 1) * L, 1], pos(g), w.rope_dims, w.rope_theta) for g in range(3)]
+    vb = [qkv[g * L:(g + 1) * L, 2] for g in range(3)]
+    qb = [orc.rope3d(qkv[g * L:(g + 1) * L, 0], pos(g), w.rope_dims, w.rope_theta) for g in (1, 2)]
+    vis = orc.visibility([orc.CLEAN, orc.NOISY, orc.NOISY], [0, 1, 2], [1, 2], mode)
+    o = np.concatenate(orc.cascade_attention(qb, kb, vb, vis)).reshape(2 * L, width)
+    ref = orc.layer_linear(o, W.to_f64(w_out))
+    Hn.assert_close(got, ref, "bf16", f"layer pipeline mode={mode}", max_abs=0.05 * float(np.abs(ref).max()) + 1e-3, rel=1e-2)
