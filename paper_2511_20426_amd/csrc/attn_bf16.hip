@@ -310,14 +310,9 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
   // Tail balancing.  One workgroup occupies a CU, an XCD has n_cu/8 of them, and all items of a
   // launch take about the same time: after floor(items / cus) full rounds, `rem` items would run
   // alone while the other CUs idle.  Their KV walks are cut into split = floor(cus / rem) ranges.
-  static int cus_per_xcd = 0;
-  if (cus_per_xcd == 0) {
-    int dev = 0, n_cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-      return finish_launch("hipDeviceGetAttribute");
-    cus_per_xcd = n_cu >= 8 ? n_cu / 8 : 1;
-  }
+  int n_cu = 0;
+  if (const int32_t rc = device_cu_count(&n_cu); rc != CA_OK) return rc;
+  const int cus_per_xcd = n_cu >= 8 ? n_cu / 8 : 1;
   a.split = 1;
   a.split_items = 0;
   a.full_items = a.work_per_xcd;
@@ -335,13 +330,9 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
     }
   }
   const dim3 grid((unsigned)((a.full_items + a.split_items * a.split) * 8));
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(attn_bf16_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 4 * kPageBytes) != hipSuccess)
-      return finish_launch("hipFuncSetAttribute");
-    attr_set = true;
-  }
+  if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void*>(attn_bf16_kernel), 4 * kPageBytes, 0);
+      rc != CA_OK)
+    return rc;
   hipLaunchKernelGGL(attn_bf16_kernel, grid, dim3(256), 4 * kPageBytes, static_cast<hipStream_t>(stream), a);
   if (a.split > 1)
     hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(8 * a.split_items)), dim3(256), 0,

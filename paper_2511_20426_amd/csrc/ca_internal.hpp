@@ -100,6 +100,11 @@ int32_t run_mfma_microbench(int data_kind, int trips, void* scratch, size_t scra
                             double* tflops, double* clock_ghz);
 int32_t launch_gemm_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                          int64_t ldx, int64_t ldw, int64_t ldy, void* stream);
+// Per-device facts and one-time kernel attributes, cached for up to kMaxDevices devices (thread
+// safe: the cached values are idempotent and written with relaxed atomics).
+constexpr int kMaxDevices = 64;
+int32_t device_cu_count(int* n_cu);                                   // of the current device
+int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot);  // slot: 0 attention, 1 GEMM
 int32_t finish_launch(const char* what);
 const char* last_device_error();
 

@@ -131,13 +131,8 @@ int32_t launch_gemm_bf16(const void* x, const void* w, void* y, int64_t M, int32
   a.sb_cols = (a.tiles_n + kSbCols - 1) / kSbCols;
   a.n_sb = ((a.tiles_m + kSbRows - 1) / kSbRows) * a.sb_cols;
   const unsigned rounds = unsigned((a.n_sb + 7) / 8);
-  static bool attr_set = false;
-  if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds) != hipSuccess)
-      return finish_launch("hipFuncSetAttribute");
-    attr_set = true;
-  }
+  if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void*>(gemm_bf16_kernel), kGemmLds, 1); rc != CA_OK)
+    return rc;
   hipLaunchKernelGGL(gemm_bf16_kernel, dim3(rounds * 8 * 32), dim3(256), kGemmLds,
                      static_cast<hipStream_t>(stream), a);
   return finish_launch("gemm_bf16.hip");

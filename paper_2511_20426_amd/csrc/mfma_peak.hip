@@ -78,11 +78,9 @@ __global__ __launch_bounds__(256, 1) void mfma_peak_kernel(int data_kind, int tr
 
 int32_t run_mfma_microbench(int data_kind, int trips, void* scratch, size_t scratch_bytes, void* stream,
                             double* tflops, double* clock_ghz) {
-  int dev = 0, n_cu = 0;
-  if (hipGetDevice(&dev) != hipSuccess ||
-      hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
-    return finish_launch("hipDeviceGetAttribute");
-  if (n_cu <= 0 || scratch_bytes < size_t(n_cu) * 16) return CA_EINVAL;
+  int n_cu = 0;
+  if (const int32_t rc = device_cu_count(&n_cu); rc != CA_OK) return rc;
+  if (scratch_bytes < size_t(n_cu) * 16) return CA_EINVAL;
   auto* probe = static_cast<unsigned long long*>(scratch);
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipEvent_t e0, e1;

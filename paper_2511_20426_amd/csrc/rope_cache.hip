@@ -9,6 +9,8 @@
 // layer (Sec. 3.3); rotary embedding is the Wan-family convention (see cascade_attn.h).
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include <cstdio>
 
 #include "ca_internal.hpp"
@@ -248,6 +250,37 @@ int32_t finish_launch(const char* what) {
 }
 
 const char* last_device_error() { return g_last_error; }
+
+namespace {
+std::atomic<int> g_cu_count[kMaxDevices];
+std::atomic<int> g_lds_set[2][kMaxDevices];
+}  // namespace
+
+int32_t device_cu_count(int* n_cu) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return finish_launch("hipGetDevice");
+  const bool cached = dev >= 0 && dev < kMaxDevices;
+  int n = cached ? g_cu_count[dev].load(std::memory_order_relaxed) : 0;
+  if (n == 0) {
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return finish_launch("hipDeviceGetAttribute");
+    if (n <= 0) return CA_EDEVICE;
+    if (cached) g_cu_count[dev].store(n, std::memory_order_relaxed);
+  }
+  *n_cu = n;
+  return CA_OK;
+}
+
+int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return finish_launch("hipGetDevice");
+  const bool cached = dev >= 0 && dev < kMaxDevices;
+  if (cached && g_lds_set[slot][dev].load(std::memory_order_relaxed) == bytes) return CA_OK;
+  if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+    return finish_launch("hipFuncSetAttribute");
+  if (cached) g_lds_set[slot][dev].store(bytes, std::memory_order_relaxed);
+  return CA_OK;
+}
 
 int32_t launch_rope_apply(const RopeGeom& g, int dtype, const void* x, void* y, int64_t n_tokens,
                           int64_t first_frame, int64_t tok_stride, int64_t head_stride,
