@@ -191,11 +191,20 @@ typedef struct {
 
 int32_t ca_sched_create(int64_t n_blocks, int32_t n_parallel, const int32_t* timesteps,
                         int32_t n_timesteps, ca_sched** out);
+/* The same walk with a lag between consecutive blocks: block j enters `lag` iterations after
+ * block j-1 and moves one timestep per iteration, so at most ceil(n_timesteps / lag) blocks are in
+ * flight.  lag 1 is Algorithm 1; lag = n_timesteps is sequential generation; for the five-entry
+ * timestep list, lag 5, 3, 2, 1 give the 1-, 2-, 3- and 5-block cascades of the ablation
+ * (Sec. 4.2, Fig. 7).  1 <= lag <= n_timesteps, any n_blocks >= 1. */
+int32_t ca_sched_create_lagged(int64_t n_blocks, const int32_t* timesteps, int32_t n_timesteps, int32_t lag,
+                               ca_sched** out);
 int32_t ca_sched_destroy(ca_sched* s);
 /* The batch of the current iteration, oldest block first; *n_out == 0 once the rollout is over. */
 int32_t ca_sched_batch(const ca_sched* s, ca_sched_entry* out, int32_t cap, int32_t* n_out);
 /* After the forward of the current batch (Alg. 1, lines 12-24): which block ran at t0 and is
- * emitted (-1 if none), which block completed tc (-1 if none); then advance (b, tau, d). */
+ * emitted (-1 if none), which block completed tc (-1 if none); then advance (b, tau, d).
+ * ca_sched_state: b = oldest block in flight, tau = its timestep index, d = batch size - 1
+ * (-1 once the rollout is over); with lag 1 these are Alg. 1's state variables. */
 int32_t ca_sched_advance(ca_sched* s, int64_t* emitted_block, int64_t* completed_block);
 int32_t ca_sched_state(const ca_sched* s, int64_t* b, int32_t* tau, int32_t* d, int64_t* iteration);
 

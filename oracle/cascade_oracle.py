@@ -295,3 +295,16 @@ def layer_linear(x: np.ndarray, w: np.ndarray) -> np.ndarray:
     w = np.asarray(w, dtype=np.float64)
     assert x.ndim == 2 and w.ndim == 2 and x.shape[1] == w.shape[1]
     return x @ w.T
+
+
+def cascade_type_schedule(n_blocks: int, n_timesteps: int, lag: int):
+    """Batches of a cascade in which block j enters `lag` iterations after block j-1 and moves
+    one timestep per iteration: iteration n forwards every block j with 0 <= n - lag*j <
+    n_timesteps at timestep index n - lag*j.  lag = 1 is Alg. 1 (five blocks in flight for the
+    five-entry timestep list); lag = n_timesteps is sequential block-causal generation (P1 of the
+    ablation, Sec. 4.2 / Fig. 7); lag 3 and 2 give the 2- and 3-block cascades.  Written as the
+    closed form, not as a state machine.  Returns [[(block, timestep index), ...] per iteration]."""
+    out = []
+    for n in range(lag * (n_blocks - 1) + n_timesteps):
+        out.append([(j, n - lag * j) for j in range(n_blocks) if 0 <= n - lag * j < n_timesteps])
+    return out

@@ -29,7 +29,7 @@ EXPORTS = (
     "rope3d_apply", "cascade_attn_forward", "ca_debug_visibility", "ca_set_kernel_variant",
     "ca_strerror", "ca_last_device_error",
     "ca_mfma_microbench", "layer_linear_bf16",
-    "ca_sched_create", "ca_sched_destroy", "ca_sched_batch", "ca_sched_advance", "ca_sched_state",
+    "ca_sched_create", "ca_sched_create_lagged", "ca_sched_destroy", "ca_sched_batch", "ca_sched_advance", "ca_sched_state",
 )
 
 
@@ -103,6 +103,8 @@ def _load() -> C.CDLL:
     lib.layer_linear_bf16.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, i64, vp]
     lib.ca_sched_create.restype = i32
     lib.ca_sched_create.argtypes = [i64, i32, C.POINTER(i32), i32, C.POINTER(vp)]
+    lib.ca_sched_create_lagged.restype = i32
+    lib.ca_sched_create_lagged.argtypes = [i64, C.POINTER(i32), i32, i32, C.POINTER(vp)]
     lib.ca_sched_destroy.restype = i32
     lib.ca_sched_destroy.argtypes = [vp]
     lib.ca_sched_batch.restype = i32
@@ -252,10 +254,14 @@ def mfma_microbench(data_kind: int, trips: int, scratch_ptr: int, scratch_bytes:
 class Scheduler:
     """Thin owner of a ca_sched* (Algorithm 1 control flow)."""
 
-    def __init__(self, n_blocks: int, n_parallel: int, timesteps: Sequence[int]):
+    def __init__(self, n_blocks: int, n_parallel: int, timesteps: Sequence[int], lag: Optional[int] = None):
+        """lag None: Alg. 1 with n_parallel blocks; otherwise the lagged walk (n_parallel ignored)."""
         ts = (C.c_int32 * len(timesteps))(*timesteps)
         h = C.c_void_p()
-        _check(lib.ca_sched_create(n_blocks, n_parallel, ts, len(timesteps), C.byref(h)), "ca_sched_create")
+        if lag is None:
+            _check(lib.ca_sched_create(n_blocks, n_parallel, ts, len(timesteps), C.byref(h)), "ca_sched_create")
+        else:
+            _check(lib.ca_sched_create_lagged(n_blocks, ts, len(timesteps), lag, C.byref(h)), "ca_sched_create_lagged")
         self._h = h
 
     def close(self) -> None:

@@ -1,12 +1,16 @@
 // Host-side cascade scheduler: the control flow of Algorithm 1 ("Multi-GPU Inference with Block
-// Cascading"), integers only.  State (b, tau, d): primary block, timestep index of the primary
-// block, cascade depth.  An iteration forwards blocks b .. b+min(d, G-1), block b+i at timestep
-// T[tau - i]; afterwards a block that ran at t0 (the second-to-last entry of T) is emitted, a block
-// that ran at tc (the last entry) is complete, and the state advances as in the listing.
+// Cascading"), integers only, generalised by the lag between consecutive blocks.
 //
-// The listing is self-consistent only when the number of parallel blocks G equals the number of
-// timesteps (otherwise a new block would enter in the middle of the schedule), and it ramps the
-// depth past the last block when there are fewer blocks than G; both cases are rejected here.
+// Every block walks the timestep list T one entry per iteration; block j enters `lag` iterations
+// after block j-1.  In iteration n the batch therefore holds the blocks j with
+// 0 <= n - lag*j < |T|, block j at T[n - lag*j] (older blocks are cleaner); a block that ran at t0
+// (the second-to-last entry of T) is emitted, one that ran at tc (the last entry) is complete.
+// lag = 1 is Algorithm 1 as listed with G = |T| parallel blocks: state (b, tau, d) = (oldest block
+// in flight, its timestep index, batch size - 1) then takes exactly the listing's values.  The
+// listing itself is self-consistent only for G = |T| (otherwise a new block would enter in the
+// middle of the schedule), so other degrees of cascading are expressed through the lag instead:
+// lag = 5, 3, 2, 1 keep at most 1, 2, 3, 5 blocks in flight (the cascade types P1..P4 of the
+// ablation, Sec. 4.2 / Fig. 7, as far as the text fixes them).
 #include <new>
 #include <vector>
 
@@ -14,30 +18,50 @@
 
 struct ca_sched {
   int64_t n_blocks;
-  int32_t n_parallel;
+  int32_t lag;
   std::vector<int32_t> timesteps;
-  int64_t b;
-  int32_t tau, d;
-  int64_t iteration;
+  int64_t iteration;                                    // n
 };
+
+namespace {
+
+int64_t last_iteration(const ca_sched* s) {
+  return int64_t(s->lag) * (s->n_blocks - 1) + int64_t(s->timesteps.size()) - 1;
+}
+
+// blocks in flight in iteration n: first (oldest) block and count
+void batch_range(const ca_sched* s, int64_t n, int64_t* first, int32_t* count) {
+  const int64_t nT = int64_t(s->timesteps.size());
+  // n - lag*j <= nT - 1  <=>  j >= (n - nT + 1) / lag (rounded up);  n - lag*j >= 0  <=>  j <= n / lag
+  int64_t lo = n - nT + 1 <= 0 ? 0 : (n - nT + 1 + s->lag - 1) / s->lag;
+  int64_t hi = n / s->lag;
+  if (hi > s->n_blocks - 1) hi = s->n_blocks - 1;
+  *first = lo;
+  *count = hi >= lo ? int32_t(hi - lo + 1) : 0;
+}
+
+}  // namespace
 
 extern "C" {
 
-int32_t ca_sched_create(int64_t n_blocks, int32_t n_parallel, const int32_t* timesteps,
-                        int32_t n_timesteps, ca_sched** out) {
-  if (!out || !timesteps || n_timesteps < 2 || n_parallel < 1 || n_blocks < 1) return CA_EINVAL;
-  if (n_parallel != n_timesteps || n_blocks < n_parallel) return CA_EUNSUPPORTED;
+int32_t ca_sched_create_lagged(int64_t n_blocks, const int32_t* timesteps, int32_t n_timesteps, int32_t lag,
+                               ca_sched** out) {
+  if (!out || !timesteps || n_timesteps < 2 || n_blocks < 1 || lag < 1 || lag > n_timesteps) return CA_EINVAL;
   ca_sched* s = new (std::nothrow) ca_sched();
   if (!s) return CA_EINVAL;
   s->n_blocks = n_blocks;
-  s->n_parallel = n_parallel;
+  s->lag = lag;
   s->timesteps.assign(timesteps, timesteps + n_timesteps);
-  s->b = 0;
-  s->tau = 0;
-  s->d = 0;
   s->iteration = 0;
   *out = s;
   return CA_OK;
+}
+
+int32_t ca_sched_create(int64_t n_blocks, int32_t n_parallel, const int32_t* timesteps, int32_t n_timesteps,
+                        ca_sched** out) {
+  if (!out || !timesteps || n_timesteps < 2 || n_parallel < 1 || n_blocks < 1) return CA_EINVAL;
+  if (n_parallel != n_timesteps || n_blocks < n_parallel) return CA_EUNSUPPORTED;
+  return ca_sched_create_lagged(n_blocks, timesteps, n_timesteps, 1, out);
 }
 
 int32_t ca_sched_destroy(ca_sched* s) {
@@ -48,16 +72,19 @@ int32_t ca_sched_destroy(ca_sched* s) {
 
 int32_t ca_sched_batch(const ca_sched* s, ca_sched_entry* out, int32_t cap, int32_t* n_out) {
   if (!s || !n_out || cap < 0 || (cap > 0 && !out)) return CA_EINVAL;
-  if (s->d < 0) {                       // rollout complete
+  if (s->iteration > last_iteration(s)) {               // rollout complete
     *n_out = 0;
     return CA_OK;
   }
-  const int32_t n = (s->d < s->n_parallel - 1 ? s->d : s->n_parallel - 1) + 1;
+  int64_t first;
+  int32_t n;
+  batch_range(s, s->iteration, &first, &n);
   if (cap < n) return CA_EINVAL;
   for (int32_t i = 0; i < n; ++i) {
-    out[i].block_id = s->b + i;
-    out[i].timestep_index = s->tau - i;
-    out[i].timestep = s->timesteps[s->tau - i];
+    const int32_t idx = int32_t(s->iteration - int64_t(s->lag) * (first + i));
+    out[i].block_id = first + i;
+    out[i].timestep_index = idx;
+    out[i].timestep = s->timesteps[idx];
   }
   *n_out = n;
   return CA_OK;
@@ -65,19 +92,16 @@ int32_t ca_sched_batch(const ca_sched* s, ca_sched_entry* out, int32_t cap, int3
 
 int32_t ca_sched_advance(ca_sched* s, int64_t* emitted_block, int64_t* completed_block) {
   if (!s) return CA_EINVAL;
-  if (s->d < 0) return CA_ESTATE;
+  if (s->iteration > last_iteration(s)) return CA_ESTATE;
   const int32_t nT = int32_t(s->timesteps.size());
-  const int32_t n = (s->d < s->n_parallel - 1 ? s->d : s->n_parallel - 1) + 1;
+  int64_t first;
+  int32_t n;
+  batch_range(s, s->iteration, &first, &n);
   int64_t emitted = -1, completed = -1;
-  for (int32_t j = 0; j < n; ++j)
-    if (s->tau - j == nT - 2) emitted = s->b + j;      // ran at t0: its prediction is the output
-  if (s->tau == nT - 1) {                               // block b completed tc
-    completed = s->b;
-    s->b += 1;
-    if (s->b + s->d >= s->n_blocks) s->d -= 1;
-  } else {
-    s->d = s->d + 1 < s->n_parallel - 1 ? s->d + 1 : s->n_parallel - 1;
-    s->tau += 1;
+  for (int32_t i = 0; i < n; ++i) {
+    const int64_t idx = s->iteration - int64_t(s->lag) * (first + i);
+    if (idx == nT - 2) emitted = first + i;             // ran at t0: its prediction is the output
+    if (idx == nT - 1) completed = first + i;           // ran at tc
   }
   s->iteration += 1;
   if (emitted_block) *emitted_block = emitted;
@@ -87,9 +111,12 @@ int32_t ca_sched_advance(ca_sched* s, int64_t* emitted_block, int64_t* completed
 
 int32_t ca_sched_state(const ca_sched* s, int64_t* b, int32_t* tau, int32_t* d, int64_t* iteration) {
   if (!s) return CA_EINVAL;
-  if (b) *b = s->b;
-  if (tau) *tau = s->tau;
-  if (d) *d = s->d;
+  int64_t first = s->n_blocks;
+  int32_t n = 0;
+  if (s->iteration <= last_iteration(s)) batch_range(s, s->iteration, &first, &n);
+  if (b) *b = first;
+  if (tau) *tau = n ? int32_t(s->iteration - int64_t(s->lag) * first) : int32_t(s->timesteps.size()) - 1;
+  if (d) *d = n - 1;
   if (iteration) *iteration = s->iteration;
   return CA_OK;
 }

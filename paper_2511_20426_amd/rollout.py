@@ -55,11 +55,12 @@ class CascadeRollout:
     mode: int = B.CA_BIDIRECTIONAL
     window_blocks: Optional[int] = None        # clean blocks kept; default: the pool's window
     epoch: int = 0
+    lag: Optional[int] = None                  # None: Alg. 1; otherwise the lagged cascade (5, 3, 2: P1..P3)
     timed: bool = False
     records: List[IterationRecord] = field(default_factory=list)
 
     def __post_init__(self):
-        self.sched = B.Scheduler(self.n_blocks, len(self.timesteps), list(self.timesteps))
+        self.sched = B.Scheduler(self.n_blocks, len(self.timesteps), list(self.timesteps), lag=self.lag)
         cfg = self.pool.cfg
         self._window = cfg.window_blocks if self.window_blocks is None else self.window_blocks
         if self._window > cfg.window_blocks:
@@ -148,6 +149,9 @@ def main(argv=None) -> None:
                          "of the paper's accounting, 5 in flight + 2 cached)")
     ap.add_argument("--mode", choices=("bidirectional", "block_causal"), default="bidirectional")
     ap.add_argument("--repeats", type=int, default=3)
+    ap.add_argument("--lag", type=int, default=None,
+                    help="iterations between consecutive blocks: 5, 3, 2, 1 = the 1-, 2-, 3-, 5-block cascades "
+                         "P1..P4 (default: Alg. 1 = 1)")
     ap.add_argument("--layer", action="store_true",
                     help="include the QKV and output projections (synthetic weights) in every iteration")
     a = ap.parse_args(argv)
@@ -186,7 +190,7 @@ def main(argv=None) -> None:
     rates, steady_ms = [], []
     for rep in range(a.repeats + 1):                      # first pass warms up
         pool = CascadePool.for_workload(pool_w)
-        ro = CascadeRollout(pool, a.blocks, W.TIMESTEPS, lambda g, ti, it, i: bank[i], mode=mode, timed=True, **hooks)
+        ro = CascadeRollout(pool, a.blocks, W.TIMESTEPS, lambda g, ti, it, i: bank[i], mode=mode, timed=True, lag=a.lag, **hooks)
         recs = ro.run()
         if rep:
             rates.append(streaming_rate(recs))
@@ -198,7 +202,8 @@ def main(argv=None) -> None:
         "unit": "iterations/s (one attention layer%s; one block of 3 latent frames emitted per iteration)"
                 % (" with its QKV and output projections" if a.layer else ""),
         "protocol": "mean over the iterations emitting the 8th and 9th block of a %d-block rollout" % a.blocks,
-        "workload": w.name, "mode": a.mode, "clean_window_blocks": window,
+        "workload": w.name, "mode": a.mode, "clean_window_blocks": window, "lag": a.lag or 1,
+        "blocks_per_s": a.blocks / (sum(r.ms for r in recs) * 1e-3),
         "iteration_ms": steady_ms, "iterations": len(recs), "data": "synthetic",
     }))
 

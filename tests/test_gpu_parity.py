@@ -378,19 +378,20 @@ def test_c5_rollout_ring_buffer():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("mode", [BI, CA])
-def test_algorithm1_rollout_driver(mode):
-    """A full 13-block rollout driven by the library's Alg. 1 scheduler (ramp-up, steady state,
-    drain) on a small token grid, 1 sink block + 2-block window: every output row of every
-    iteration against the oracle, which follows its own transcription of Alg. 1 and its own
-    cache state machine."""
+@pytest.mark.parametrize("mode,lag", [(BI, None), (CA, None), (BI, 2), (CA, 3), (BI, 5)])
+def test_algorithm1_rollout_driver(mode, lag):
+    """A full 13-block rollout driven by the library's scheduler (ramp-up, steady state, drain) on
+    a small token grid, 1 sink block + 2-block window: every output row of every iteration
+    against the oracle, which follows its own transcription of Alg. 1 (lag None) or its closed
+    form of the lagged cascades (lag 2, 3, 5: three, two, one block in flight) and its own cache
+    state machine."""
     import torch
     from paper_2511_20426_amd.runner import CascadePool
     from paper_2511_20426_amd.rollout import CascadeRollout
     w = W.small_variant(W.CONFIGS["c5_wan1p3b_rollout"], heads=2, grid_h=6, grid_w=9, window_blocks=2)
     L, H = w.block_tokens, w.heads
     n_blocks = 13
-    _say(f"alg1 rollout driver: L={L} heads={H} mode={mode}")
+    _say(f"alg1 rollout driver: L={L} heads={H} mode={mode} lag={lag}")
     pool = CascadePool.for_workload(w)
     host, outs = {}, {}
 
@@ -401,9 +402,13 @@ def test_algorithm1_rollout_driver(mode):
     def out_fn(g, ti, o):
         outs.setdefault(len(ro.records), []).append(Hn.from_torch(o, w.dtype))
 
-    ro = CascadeRollout(pool, n_blocks, W.TIMESTEPS, qkv_fn, out_fn, mode=mode)
-    trace = orc.algorithm1_trace(n_blocks, 5)
-    assert len(trace) == n_blocks + 4
+    ro = CascadeRollout(pool, n_blocks, W.TIMESTEPS, qkv_fn, out_fn, mode=mode, lag=lag)
+    if lag is None:
+        trace = orc.algorithm1_trace(n_blocks, 5)
+        assert len(trace) == n_blocks + 4
+    else:
+        trace = [(batch[0][0], batch[0][1], len(batch) - 1, batch) for batch in orc.cascade_type_schedule(n_blocks, 5, lag)]
+        assert len(trace) == lag * (n_blocks - 1) + 5
     cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, w.max_inflight, w.pages_per_block, H)
     pos = lambda g: orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w)
     final_kv = {}

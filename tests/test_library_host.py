@@ -215,3 +215,29 @@ def test_scheduler_matches_algorithm1_trace_and_golden():
     with pytest.raises(B.CascadeAttnError) as ex:
         B.Scheduler(0, 5, T)
     assert ex.value.code == B.CA_EINVAL
+
+
+def test_lagged_scheduler_matches_closed_form():
+    """ca_sched_create_lagged against the oracle's closed form for the cascade types (lag 5, 3, 2, 1)
+    and an uneven lag; emitted / completed blocks in order; argument checks."""
+    T = list(W.TIMESTEPS)
+    for lag in (1, 2, 3, 4, 5):
+        for n_blocks in (1, 2, 7, 13):
+            ref = orc.cascade_type_schedule(n_blocks, len(T), lag)
+            s = B.Scheduler(n_blocks, 0, T, lag=lag)
+            emitted, completed = [], []
+            for n, batch in enumerate(ref):
+                assert s.batch() == [(g, ti, T[ti]) for g, ti in batch]
+                b, tau, d, it = s.state()
+                assert (b, tau, d, it) == (batch[0][0], batch[0][1], len(batch) - 1, n)
+                e, c = s.advance()
+                assert e == next((g for g, ti in batch if ti == len(T) - 2), -1)
+                assert c == next((g for g, ti in batch if ti == len(T) - 1), -1)
+                emitted += [e] if e >= 0 else []
+                completed += [c] if c >= 0 else []
+            assert s.batch() == [] and s.state()[2] == -1
+            assert emitted == completed == list(range(n_blocks))
+    for bad in (0, 6):
+        with pytest.raises(B.CascadeAttnError) as ex:
+            B.Scheduler(5, 0, T, lag=bad)
+        assert ex.value.code == B.CA_EINVAL

@@ -471,3 +471,26 @@ def test_layer_linear_against_the_definition_and_special_cases():
     np.testing.assert_allclose(orc.layer_linear(x + 2 * x2, w), orc.layer_linear(x, w) + 2 * orc.layer_linear(x2, w), rtol=1e-12, atol=1e-12)
     np.testing.assert_allclose(orc.layer_linear(x, w - w2), orc.layer_linear(x, w) - orc.layer_linear(x, w2), rtol=1e-12, atol=1e-12)
     assert orc.layer_linear(x, w).shape == (5, 4)            # [rows, out], weights stored [out, in]
+
+
+def test_cascade_type_schedule_properties():
+    """lag 1 is Alg. 1's batch sequence; for any lag every block visits every timestep once, in
+    order, one per iteration; consecutive blocks are `lag` iterations apart; at most
+    ceil(|T| / lag) blocks are in flight: 1, 2, 3, 5 for lag 5, 3, 2, 1 (P1..P4)."""
+    T = 5
+    for B in (5, 8, 13):
+        assert orc.cascade_type_schedule(B, T, 1) == [batch for _, _, _, batch in orc.algorithm1_trace(B, 5)]
+    for lag, width in ((5, 1), (3, 2), (2, 3), (1, 5), (4, 2)):
+        sch = orc.cascade_type_schedule(7, T, lag)
+        assert max(len(b) for b in sch) == width == -(-T // lag)
+        seen = {}
+        for n, batch in enumerate(sch):
+            assert batch == sorted(batch)                               # oldest block first
+            for j, idx in batch:
+                seen.setdefault(j, []).append((n, idx))
+        assert sorted(seen) == list(range(7))
+        for j, visits in seen.items():
+            assert [idx for _, idx in visits] == list(range(T))
+            assert [n for n, _ in visits] == list(range(lag * j, lag * j + T))
+        assert len(sch) == lag * 6 + T
+    assert orc.cascade_type_schedule(3, T, 5) == [[(j, i)] for j in range(3) for i in range(T)]   # sequential
