@@ -163,16 +163,26 @@ __global__ __launch_bounds__(256) void rope_generic_kernel(RopeGeom g, GenericAr
 constexpr int kPage = 128;
 constexpr int kVRowWords = 65;
 
+// cos/sin are shared by every head of a token and, per axis, by every token with the same frame,
+// row or column: a workgroup tabulates them once per axis value present in its page (for a
+// 128-token page of a 30 x 52 grid: 2 frames x 22 pairs + 4 rows x 21 + 52 columns x 21 = 1220
+// evaluations instead of 128 tokens x 64 pairs = 8192) and its threads pick theirs from LDS.
+struct TrigTable {
+  int32_t n_f, n_y, n_x;       // axis values tabulated: consecutive frames / rows (mod grid_h) / columns (mod grid_w)
+};
+
 struct PagedArgs {
   const uint16_t* k;
   const uint16_t* v;
   uint8_t* pool;
   int64_t tok_stride, head_stride, first_frame;
   int32_t block_tokens, pages_per_block, slot, heads_per_group;
+  TrigTable tab;               // n_f == 0: no table (geometry too large for LDS), evaluate per thread
 };
 
 __global__ __launch_bounds__(256) void cache_write_bf16_kernel(RopeGeom g, PagedArgs a) {
   __shared__ uint32_t vt[kPage * kVRowWords];
+  extern __shared__ float2 trig[];   // [n_f][pairs_t] then [n_y][pairs_h] then [n_x][pairs_w]
   const int t = threadIdx.x;
   const int page = blockIdx.x;
   const int c = t & 15;              // chunk owned by this thread (K: dims 8c..8c+7; V: 8 tokens)
@@ -181,12 +191,54 @@ __global__ __launch_bounds__(256) void cache_write_bf16_kernel(RopeGeom g, Paged
 
   // cos/sin of this thread's 4 pairs at its 8 tokens
   float cs[8][4], sn[8][4];
+  if (a.tab.n_f > 0) {
+    const int pairs_w = g.head_dim / 2 - g.pairs_t - g.pairs_h;
+    const TokenPos first = token_pos(min(tok0, a.block_tokens - 1), a.first_frame, g.grid_h, g.grid_w);
+    const int off_y = a.tab.n_f * g.pairs_t, off_x = off_y + a.tab.n_y * g.pairs_h;
+    const int total = off_x + a.tab.n_x * pairs_w;
+    for (int e = t; e < total; e += 256) {
+      TokenPos p = first;
+      int pair;
+      if (e < off_y) {
+        p.f = first.f + e / g.pairs_t;
+        pair = e % g.pairs_t;
+      } else if (e < off_x) {
+        p.y = (first.y + (e - off_y) / g.pairs_h) % g.grid_h;
+        pair = g.pairs_t + (e - off_y) % g.pairs_h;
+      } else {
+        p.x = (first.x + (e - off_x) / pairs_w) % g.grid_w;
+        pair = g.pairs_t + g.pairs_h + (e - off_x) % pairs_w;
+      }
+      float cv, sv;
+      pair_cs<false>(g, p, pair, &cv, &sv);
+      trig[e] = make_float2(cv, sv);
+    }
+    __syncthreads();
 #pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int n = tok0 + r0 + 16 * i;
-    const TokenPos p = token_pos(min(n, a.block_tokens - 1), a.first_frame, g.grid_h, g.grid_w);
+    for (int i = 0; i < 8; ++i) {
+      const int n = tok0 + r0 + 16 * i;
+      const TokenPos p = token_pos(min(n, a.block_tokens - 1), a.first_frame, g.grid_h, g.grid_w);
+      const int rf = p.f - first.f;
+      const int ry = (p.y - first.y + g.grid_h) % g.grid_h, rx = (p.x - first.x + g.grid_w) % g.grid_w;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) pair_cs<false>(g, p, c * 4 + j, &cs[i][j], &sn[i][j]);
+      for (int j = 0; j < 4; ++j) {
+        const int pair = c * 4 + j;
+        const int e = pair < g.pairs_t ? rf * g.pairs_t + pair
+                      : (pair < g.pairs_t + g.pairs_h ? off_y + ry * g.pairs_h + (pair - g.pairs_t)
+                                                      : off_x + rx * pairs_w + (pair - g.pairs_t - g.pairs_h));
+        const float2 v = trig[e];
+        cs[i][j] = v.x;
+        sn[i][j] = v.y;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int n = tok0 + r0 + 16 * i;
+      const TokenPos p = token_pos(min(n, a.block_tokens - 1), a.first_frame, g.grid_h, g.grid_w);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) pair_cs<false>(g, p, c * 4 + j, &cs[i][j], &sn[i][j]);
+    }
   }
 
   const int h0 = blockIdx.y * a.heads_per_group;
@@ -325,7 +377,21 @@ int32_t launch_cache_write(const RopeGeom& g, int dtype, const void* k, const vo
     a.heads_per_group = (g.heads + groups - 1) / groups;
     const dim3 grid((unsigned)pages_per_block,
                     (unsigned)((g.heads + a.heads_per_group - 1) / a.heads_per_group));
-    hipLaunchKernelGGL(cache_write_bf16_kernel, grid, dim3(256), 0, s, g, a);
+    // axis values a 128-token page can touch: consecutive tokens, so consecutive columns (all of
+    // them once the page is longer than a row), rows and frames
+    const int plane = g.grid_h * g.grid_w;
+    TrigTable tab;
+    tab.n_x = g.grid_w < kPage ? g.grid_w : kPage;
+    tab.n_y = kPage / g.grid_w + 2 < g.grid_h ? kPage / g.grid_w + 2 : g.grid_h;
+    tab.n_f = kPage / plane + 2;
+    const int pairs_w = g.head_dim / 2 - g.pairs_t - g.pairs_h;
+    size_t tab_bytes = sizeof(float2) * (size_t(tab.n_f) * g.pairs_t + size_t(tab.n_y) * g.pairs_h + size_t(tab.n_x) * pairs_w);
+    if (tab_bytes > 16384) {
+      tab.n_f = 0;
+      tab_bytes = 0;
+    }
+    a.tab = tab;
+    hipLaunchKernelGGL(cache_write_bf16_kernel, grid, dim3(256), tab_bytes, s, g, a);
   } else {
     GenericArgs a{};
     a.x = k; a.v = v; a.y = pool;
