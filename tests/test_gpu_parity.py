@@ -258,9 +258,27 @@ def _full_shape(name, modes, heads_sample, n_random):
         _say(f"{name}: oracle on {sum(len(r) for r in rows)} rows x {len(heads_sample)} heads in {time.time() - t0:.1f}s")
         got = [o[np.asarray(r)][:, list(heads_sample)] for o, r in zip(W.split_blocks(out, L), rows)]
         Hn.assert_close(np.concatenate(got), np.concatenate(ref), "bf16", f"{name} mode={mode}")
-        # property that holds for every row at any size: outputs are convex combinations of V rows
+        # properties that hold for every row at any size: outputs are convex combinations of V rows,
+        # and cutting the KV walk of the last work items into page ranges (tail balancing, merged
+        # afterwards) changes a result only through rounding: of the final bf16 (2 ulps allowed) and of
+        # the probabilities, which are rounded to bf16 against another exponent reference in each
+        # range (2^-9 relative per term, i.e. 2^-9 rms(v) / sqrt(keys) on the output; 8 sigma allowed)
         assert np.isfinite(out).all()
         assert np.abs(out).max() <= np.abs(W.bf16_bits_to_f32(v)).max()
+        pool.ctx.set_kernel_variant(1)
+        whole = Hn.gpu_forward(w, pool, q, infl, mode)
+        pool.ctx.set_kernel_variant(0)
+        gap = np.abs(out - whole)
+        _say(f"{name}: split vs whole KV walks: {int((gap > 0).sum())} of {gap.size} elements differ, "
+             f"max {float(gap.max()):.2e}")
+        v_rms = float(np.sqrt(np.mean(W.bf16_bits_to_f32(v).astype(np.float64) ** 2)))
+        keys = (w.n_cached + (1 if mode == CA else w.n_inflight)) * L
+        bound = 2.0 ** -7 * np.maximum(np.abs(out), np.abs(whole)) + 8 * 2.0 ** -9 * v_rms / np.sqrt(keys)
+        bad = np.argwhere(gap > bound)
+        if len(bad):
+            i = tuple(bad[0])
+            _say(f"{name}: {len(bad)} outside the bound, first at {i}: {out[i]!r} vs {whole[i]!r}")
+        assert len(bad) == 0
 
 
 def test_c2_wan1p3b_sequential_sampled():
