@@ -152,6 +152,8 @@ SMALL = [
     (1, 8, 16, 0, 5),       # 384  = exactly 3 pages, no cache at all
     (5, 13, 11, 3, 1),      # 429  : single in-flight block (cascade P1)
     (2, 19, 27, 1, 2),      # 1539 : several 256-row tiles per block + ragged rows and keys
+    (1, 4, 5, 0, 1),        # 60   : the whole KV sequence is one ragged page
+    (1, 8, 16, 3, 1),       # 384  : one block of queries on a cache of full pages only
 ]
 
 
