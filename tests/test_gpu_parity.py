@@ -196,6 +196,20 @@ def test_bf16_moving_row_maximum(mode, ramp, bar):
     Hn.assert_close(got, want, "bf16", f"moving maximum {ramp}", max_abs=bar * float(np.abs(want).max()) * 4, rel=bar)
 
 
+@pytest.mark.parametrize("gh,gw", [(3, 43), (3, 53), (10, 16), (7, 23), (12, 16), (223, 1), (14, 16), (15, 15),
+                                   (15, 17), (16, 16)])
+def test_bf16_every_ragged_tail_class(gh, gw):
+    """One frame per block, so that the block length L = gh * gw can take any value: the valid
+    keys of the last page (L mod 128 = 1, 31, 32, 33, 64, 95, 96, 97, 127, 0) straddle every
+    32-key step boundary of the page, in both masking modes, with two blocks of queries."""
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=gh, grid_w=gw, frames_per_block=1,
+                        n_cached=1, n_inflight=2)
+    _say(f"bf16 ragged tail class L={w.block_tokens} (mod 128 = {w.block_tokens % 128})")
+    for mode in (BI, CA):
+        outs, ref = _one_shot(w, mode, seed=61, first_block=3)
+        Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", f"ragged L={w.block_tokens} mode={mode}")
+
+
 def test_bf16_single_block_modes_agree_bitwise():
     """One in-flight block: both modes are the same computation (cascade P1, Fig. 7)."""
     w = W.small_variant(W.CONFIGS["c2_wan1p3b_seq"], heads=2, grid_h=9, grid_w=14, n_cached=3)
