@@ -38,7 +38,7 @@ struct GemmArgs {
 __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int l31 = lane & 31, hi = lane >> 5;
+  const int l15 = lane & 15, grp = lane >> 4;
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   const int sb = (j >> 5) * 8 + xcd, within = j & 31;
   if (sb >= a.n_sb) return;
@@ -48,13 +48,13 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
   const int m0 = tm * kTile, n0 = tn * kTile;
   const int wm = wave & 1, wn = wave >> 1;
 
-  // global -> LDS: load i of this wave fills rows (8 wave + i) 8 .. +7 of a part (128-byte rows:
-  // whole cache lines); lane L fills position L & 7 of row L >> 3, i.e. chunk (L & 7) ^ (row & 7)
+  // load i of this wave brings rows (8 wave + i) 8 .. +7 of a part (128-byte rows: whole cache
+  // lines); lane L brings what is stored at position L & 7 of row L >> 3: chunk (L & 7) ^ ((row >> 1) & 7)
   uint32_t offw[8], offx[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
     const int row = (wave * 8 + i) * 8 + (lane >> 3);
-    const int c = (lane & 7) ^ (row & 7);
+    const int c = (lane & 7) ^ ((row >> 1) & 7);
     offw[i] = uint32_t(int64_t(row) * a.ldw * 2 + c * 16);
     const int mrow = min(m0 + row, a.M - 1) - m0;                // rows past M re-read the last row
     offx[i] = uint32_t(int64_t(mrow) * a.ldx * 2 + c * 16);
@@ -63,22 +63,20 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
   const uint32_t waddr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + wave * 8192 + lane * 16;
   const uint64_t base_w = reinterpret_cast<uint64_t>(a.w + int64_t(n0) * a.ldw);
   const uint64_t base_x = reinterpret_cast<uint64_t>(a.x + int64_t(m0) * a.ldx);
-  // operand reads: row (128 bytes) of this lane in the wave's 128 rows, chunk hi of k-step 0
-  const uint32_t swz = l31 & 7;
-  const uint32_t aw0 = uint32_t((wn * 128 + l31) * 128) + ((uint32_t(hi) ^ swz) << 4);
-  const uint32_t ax0 = uint32_t((wm * 128 + l31) * 128) + ((uint32_t(hi) ^ swz) << 4);
+  // operand reads (16 x 16 x 32 MFMA: lane = row l15 of a 16-row sub-tile, 8 k-values of group
+  // grp): chunk grp of k-step 0 of the lane's row in the wave's 128 rows
+  const uint32_t swz = (l15 >> 1) & 7;
+  const uint32_t aw0 = uint32_t((wn * 128 + l15) * 128) + ((uint32_t(grp) ^ swz) << 4);
+  const uint32_t ax0 = uint32_t((wm * 128 + l15) * 128) + ((uint32_t(grp) ^ swz) << 4);
   const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
   const int wave_s = __builtin_amdgcn_readfirstlane(wave);
   const int n_stages = a.K / 64;
 
-  // o6/o7 are not early-clobber: the block copies every VGPR input in its first instructions and
-  // does not touch v[96:127] again before the epilogue; the inputs need somewhere to live (it uses
-  // all of v[128:255] as staging registers)
   u32x16 o0, o1, o2, o3, o4, o5, o6, o7;
   asm volatile(
 #include "gemm_core_gfx950.inc"
       : "=&{v[0:15]}"(o0), "=&{v[16:31]}"(o1), "=&{v[32:47]}"(o2), "=&{v[48:63]}"(o3), "=&{v[64:79]}"(o4),
-        "=&{v[80:95]}"(o5), "={v[96:111]}"(o6), "={v[112:127]}"(o7)
+        "=&{v[80:95]}"(o5), "=&{v[96:111]}"(o6), "=&{v[112:127]}"(o7)
       : [base_w] "s"(base_w), [base_x] "s"(base_x), [n_stages] "s"(n_stages), [wave] "s"(wave_s),
         [lds0] "s"(lds0), [offw0] "v"(offw[0]), [offw1] "v"(offw[1]), [offw2] "v"(offw[2]), [offw3] "v"(offw[3]),
         [offw4] "v"(offw[4]), [offw5] "v"(offw[5]), [offw6] "v"(offw[6]), [offw7] "v"(offw[7]),
@@ -88,18 +86,18 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
       : "memory", "scc", "m0", CA_GEMM_CLOBBERS);
 
   // ---- epilogue: the wave's 128 (m) x 128 (n) tile goes through LDS to come out row by row.
-  // Pair p of MFMA tile T = 4 ti + tj: n = 32 ti + 8 (p / 2) + 4 hi + 2 (p % 2), m = 32 tj + l31.
+  // Pair p of MFMA tile T = 8 ti + tj: n = 16 ti + 4 grp + 2 p, m = 16 tj + l15.
   __syncthreads();                                    // every wave is done with the stage buffers
   uint8_t* mine = lds + wave * kEpiWave;
   const u32x16 o[8] = {o0, o1, o2, o3, o4, o5, o6, o7};
 #pragma unroll
-  for (int T = 0; T < 16; ++T) {
-    const int ti = T >> 2, tj = T & 3;
+  for (int T = 0; T < 64; ++T) {
+    const int ti = T >> 3, tj = T & 7;
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      const int n = 32 * ti + 8 * (p >> 1) + 4 * hi + 2 * (p & 1);
-      const int m = 32 * tj + l31;
-      *reinterpret_cast<uint32_t*>(mine + m * kEpiRow + n * 2) = o[T >> 1][8 * (T & 1) + p];
+    for (int p = 0; p < 2; ++p) {
+      const int n = 16 * ti + 4 * grp + 2 * p;
+      const int m = 16 * tj + l15;
+      *reinterpret_cast<uint32_t*>(mine + m * kEpiRow + n * 2) = o[(2 * T + p) >> 4][(2 * T + p) & 15];
     }
   }
   __syncthreads();

@@ -59,14 +59,16 @@ def schedule(fixed_load, atoms, cap):
     n = len(fixed_load)
     placed = [[] for _ in range(n)]
     pending = list(atoms)
-    for i in range(n):
+    widest = cap - min(fixed_load)                       # an atom larger than this fits no slot:
+    for i in range(n):                                    # it takes one that holds nothing else yet
         room = cap - fixed_load[i]
         while True:
             cands = [a for a in pending if a.ready_slot() is not None and a.ready_slot() <= i]
             cands.sort(key=lambda a: a.deadline)
             pick = None
             for a in cands:
-                if a.cost <= room + 1e-9 or a.hard <= i:
+                oversize = a.cost > widest + 1e-9 and not placed[i] and room >= widest - 1e-9
+                if a.cost <= room + 1e-9 or a.hard <= i or oversize:
                     pick = a
                     break
             if pick is None:

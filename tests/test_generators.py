@@ -47,10 +47,15 @@ def test_scheduler_respects_ready_order_gaps_and_hard_deadlines():
                 assert pos[id(a)] > pos[id(dep)]                                             # issue order too
         for i, s in enumerate(placed):                                                         # no overflow: all of it fits
             assert 2.0 + sum(a.cost for a in s) <= 8.0 + 1e-9 or any(a.hard <= i for a in s)
-    # an atom that cannot fit anywhere is still placed, by its hard deadline
-    big = sched.Atom(["v_exp_f32 v1, v2"] * 5, 0, 3, hard=5)
-    placed = sched.schedule([2.0] * 8, [big], 8.0)
-    assert big.slot == 5
+    # an atom larger than any slot takes the first one that holds nothing else; one that finds no
+    # room before its hard deadline is placed there regardless
+    big = sched.Atom(["v_exp_f32 v1, v2"] * 5, 2, 3, hard=5)
+    small = [sched.Atom(["v_add_f32 v0, v0, v0"] * 6, 0, 0, hard=7) for _ in range(3)]
+    placed = sched.schedule([2.0] * 8, small + [big], 8.0)
+    assert big.slot == 3 and [a.slot for a in small] == [0, 1, 2] and placed[3] == [big]
+    late = sched.Atom(["v_add_f32 v0, v0, v0"] * 4, 0, 0, hard=1)
+    placed = sched.schedule([2.0] * 4, [sched.Atom(["v_add_f32 v0, v0, v0"] * 6, 0, 0, hard=3) for _ in range(2)] + [late], 8.0)
+    assert late.slot == 1
 
 
 def test_quanta_model():
@@ -152,28 +157,35 @@ def test_attention_cold_blocks_have_no_barrier_and_return():
 def test_gemm_stage_invariants():
     for P in range(2):
         slots = gemm.build_stage(P)
-        assert len(slots) == 64
-        text = [ln for _, lines in slots for ln in lines]
+        assert len(slots) == 128 and all(m.startswith("v_mfma_f32_16x16x32_bf16") for m, _ in slots)
+        text = [ln for m, lines in slots for ln in [m] + lines]
         reads = [ln for ln in text if ln.startswith("ds_read_b128")]
         writes = [ln for ln in text if ln.startswith("ds_write_b128")]
         loads = [ln for ln in text if ln.startswith("global_load_dwordx4")]
         assert len(reads) == 32 and len(writes) == 16 and len(loads) == 16
         assert sum(1 for ln in text if ln == "s_barrier") == 1
-        # a staging quad is written to LDS before it is refilled
+        # a staging quad goes to LDS (after a wait that lets at most the 15 younger loads fly)
+        # before it is refilled, and every quad does so once per stage
+        quads = []
         for k, ln in enumerate(text):
             if ln.startswith("global_load_dwordx4"):
                 quad = re.match(r"global_load_dwordx4 (v\[\d+:\d+\])", ln).group(1)
-                assert text[k - 1].startswith("ds_write_b128") and quad in text[k - 1]
-        # lgkm waits: as many LDS operations may be outstanding as were issued behind the last read
+                back = [x for x in text[:k] if x.startswith(("ds_write_b128", "s_waitcnt vmcnt"))]
+                assert back[-1].startswith("ds_write_b128") and quad in back[-1]
+                assert back[-2] == "s_waitcnt vmcnt(15)"
+                quads.append(quad)
+        assert len(set(quads)) == 16
+        # writes of the stage that becomes visible at the barrier are all issued before it
+        k_bar = text.index("s_barrier")
+        assert sum(1 for ln in text[:k_bar] if ln.startswith("ds_write_b128")) == 8
+        assert text[k_bar - 1] == "s_waitcnt lgkmcnt(0)"
+        # the wait that ends the stage allows no more LDS operations in flight than were issued
+        # behind the last fragment read
         k_reads = [k for k, ln in enumerate(text) if ln.startswith("ds_read_b128")]
-        for k, ln in enumerate(text):
-            m = re.match(r"s_waitcnt lgkmcnt\((\d+)\)$", ln)
-            if m:
-                last_read = max(r for r in k_reads if r < k)
-                behind = sum(1 for x in text[last_read + 1:k] if x.startswith("ds_"))
-                assert int(m.group(1)) <= behind
-        assert any(ln.startswith("s_waitcnt vmcnt(16) lgkmcnt(0)") for ln in text)
-        # MFMA k-steps alternate fragment buffers and every accumulator tile is hit once per k-step
-        for kk in range(4):
-            accs = [re.match(r"v_mfma\S+ (a\[\d+:\d+\])", m).group(1) for m, _ in slots[16 * kk:16 * kk + 16]]
-            assert len(set(accs)) == 16
+        m = re.match(r"s_waitcnt lgkmcnt\((\d+)\)$", text[-1])
+        behind = sum(1 for x in text[max(k_reads) + 1:] if x.startswith("ds_"))
+        assert m and int(m.group(1)) <= behind
+        # the two k-steps use different fragment buffers; every accumulator tile is hit once per k-step
+        for kk in range(2):
+            accs = [re.match(r"v_mfma\S+ (a\[\d+:\d+\])", m_).group(1) for m_, _ in slots[64 * kk:64 * kk + 64]]
+            assert len(set(accs)) == 64
