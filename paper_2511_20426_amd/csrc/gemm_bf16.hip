@@ -2,7 +2,7 @@
 // attention inside a DiT layer (QKV projection before it, output projection after it).
 //
 //   Workgroup = 4 waves = a 256 x 256 tile of Y, one wave per SIMD; the main loop (K in stages of
-//   64, two stages resident in LDS, loads staged through registers two to three stages ahead) is the assembly
+//   64, both operands through rings in LDS that together fill its 160 KB) is the assembly
 //   emitted by gen_gemm_core.py, which documents the pipeline and the register map.  This file
 //   holds the set-up, the epilogue (tile transposed through LDS so that rows of Y are written as
 //   256-byte runs) and the launch.
@@ -22,7 +22,8 @@ constexpr int kTile = 256;
 constexpr int kSbRows = 8, kSbCols = 4;           // tiles of one XCD's block
 constexpr int kEpiRow = 272;                      // bytes per row of a wave's 128 x 128 bf16 tile in LDS
 constexpr int kEpiWave = 128 * kEpiRow;
-constexpr int kGemmLds = 4 * kEpiWave;            // 139264 >= 4 stages x 32 KB
+constexpr int kGemmLds = 160 * 1024;              // main loop: 3 W stages + 2 X stages of 32 KB; epilogue: 4 x kEpiWave
+static_assert(4 * kEpiWave <= kGemmLds, "epilogue staging fits");
 
 struct GemmArgs {
   const uint16_t* x;
@@ -59,8 +60,6 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
     const int mrow = min(m0 + row, a.M - 1) - m0;                // rows past M re-read the last row
     offx[i] = uint32_t(int64_t(mrow) * a.ldx * 2 + c * 16);
   }
-  // where this lane's 16 bytes of load i go in a part: row (8 wave + i) 8 + (lane >> 3), position lane & 7
-  const uint32_t waddr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds)) + wave * 8192 + lane * 16;
   const uint64_t base_w = reinterpret_cast<uint64_t>(a.w + int64_t(n0) * a.ldw);
   const uint64_t base_x = reinterpret_cast<uint64_t>(a.x + int64_t(m0) * a.ldx);
   // operand reads (16 x 16 x 32 MFMA: lane = row l15 of a 16-row sub-tile, 8 k-values of group
@@ -82,7 +81,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
         [offw4] "v"(offw[4]), [offw5] "v"(offw[5]), [offw6] "v"(offw[6]), [offw7] "v"(offw[7]),
         [offx0] "v"(offx[0]), [offx1] "v"(offx[1]), [offx2] "v"(offx[2]), [offx3] "v"(offx[3]),
         [offx4] "v"(offx[4]), [offx5] "v"(offx[5]), [offx6] "v"(offx[6]), [offx7] "v"(offx[7]),
-        [aw0] "v"(aw0), [ax0] "v"(ax0), [waddr] "v"(waddr)
+        [aw0] "v"(aw0), [ax0] "v"(ax0)
       : "memory", "scc", "m0", CA_GEMM_CLOBBERS);
 
   // ---- epilogue: the wave's 128 (m) x 128 (n) tile goes through LDS to come out row by row.

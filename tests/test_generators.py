@@ -155,36 +155,41 @@ def test_attention_cold_blocks_have_no_barrier_and_return():
 
 
 def test_gemm_stage_invariants():
-    for P in range(2):
+    for P in range(gemm.PERIOD):
         slots = gemm.build_stage(P)
         assert len(slots) == 128 and all(m.startswith("v_mfma_f32_16x16x32_bf16") for m, _ in slots)
         text = [ln for m, lines in slots for ln in [m] + lines]
         reads = [ln for ln in text if ln.startswith("ds_read_b128")]
-        writes = [ln for ln in text if ln.startswith("ds_write_b128")]
-        loads = [ln for ln in text if ln.startswith("global_load_dwordx4")]
-        assert len(reads) == 32 and len(writes) == 16 and len(loads) == 16
+        loads = [k for k, ln in enumerate(text) if ln.startswith("global_load_lds_dwordx4")]
+        assert len(reads) == 32 and len(loads) == 16
         assert sum(1 for ln in text if ln == "s_barrier") == 1
-        # a staging quad goes to LDS (after a wait that lets at most the 15 younger loads fly)
-        # before it is refilled, and every quad does so once per stage
-        quads = []
-        for k, ln in enumerate(text):
-            if ln.startswith("global_load_dwordx4"):
-                quad = re.match(r"global_load_dwordx4 (v\[\d+:\d+\])", ln).group(1)
-                back = [x for x in text[:k] if x.startswith(("ds_write_b128", "s_waitcnt vmcnt"))]
-                assert back[-1].startswith("ds_write_b128") and quad in back[-1]
-                assert back[-2] == "s_waitcnt vmcnt(15)"
-                quads.append(quad)
-        assert len(set(quads)) == 16
-        # writes of the stage that becomes visible at the barrier are all issued before it
         k_bar = text.index("s_barrier")
-        assert sum(1 for ln in text[:k_bar] if ln.startswith("ds_write_b128")) == 8
-        assert text[k_bar - 1] == "s_waitcnt lgkmcnt(0)"
-        # the wait that ends the stage allows no more LDS operations in flight than were issued
-        # behind the last fragment read
-        k_reads = [k for k, ln in enumerate(text) if ln.startswith("ds_read_b128")]
-        m = re.match(r"s_waitcnt lgkmcnt\((\d+)\)$", text[-1])
-        behind = sum(1 for x in text[max(k_reads) + 1:] if x.startswith("ds_"))
-        assert m and int(m.group(1)) <= behind
+        # all loads sit behind the barrier that frees their buffers; every M0 write is directly
+        # followed by its load; W goes to ring slot (P+3) % 3, X to ring slot (P+2) % 2
+        assert min(loads) > k_bar
+        for k in loads:
+            m0 = re.match(r"s_add_u32 m0, s\d+, (\d+)$", text[k - 1])
+            assert m0, text[k - 1]
+            off = int(m0.group(1))
+            if f"s[{gemm.S_BX}:" in text[k]:
+                assert gemm.XBASE + ((P + 2) % gemm.NX) * gemm.PART <= off < gemm.XBASE + ((P + 2) % gemm.NX + 1) * gemm.PART
+            else:
+                assert ((P + 3) % gemm.NW) * gemm.PART <= off < ((P + 3) % gemm.NW + 1) * gemm.PART
+        # the wait at the barrier lets exactly the loads issued behind the last X load fly
+        kinds = ["x" if f"s[{gemm.S_BX}:" in text[k] else "w" for k in loads]
+        behind = len(kinds) - 1 - max(i for i, x in enumerate(kinds) if x == "x")
+        assert text[k_bar - 1] == f"s_waitcnt vmcnt({behind}) lgkmcnt(0)"
+        assert kinds.count("x") == 8 and kinds.count("w") == 8
+        # fragment reads: first k-step reads this stage's ring slots, second the next stage's
+        for ln in text[:k_bar]:
+            if ln.startswith("ds_read_b128"):
+                addr = int(re.search(r", v(\d+) offset", ln).group(1))
+                assert addr in (gemm.ADDRW + 2 * (P % gemm.NW) + 1, gemm.ADDRX + 2 * (P % gemm.NX) + 1)
+        for ln in text[k_bar:]:
+            if ln.startswith("ds_read_b128"):
+                addr = int(re.search(r", v(\d+) offset", ln).group(1))
+                assert addr in (gemm.ADDRW + 2 * ((P + 1) % gemm.NW), gemm.ADDRX + 2 * ((P + 1) % gemm.NX))
+        assert text[-1] == "s_waitcnt lgkmcnt(0)"
         # the two k-steps use different fragment buffers; every accumulator tile is hit once per k-step
         for kk in range(2):
             accs = [re.match(r"v_mfma\S+ (a\[\d+:\d+\])", m_).group(1) for m_, _ in slots[64 * kk:64 * kk + 64]]
