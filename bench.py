@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2516.6        # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
 # HBM bytes per attention launch at the Wan-14B shape, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # scaled by a 1 GiB copy (profiles/c4_wan14b_cascade5_hbm_traffic.txt): 4295.3 MB read + 259.6 MB written
 # by the attention kernel, 26.2 + 8.3 MB by the merge of its split work items
@@ -206,14 +207,20 @@ def main() -> int:
     state = {"b": w.n_cached}
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
           for _ in range(args.steps)]
+    ev_a = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
 
     def step(i_timed=None):
         b = state["b"]
         infl = list(range(b, b + C))
+        if i_timed is not None:
+            ev_a[i_timed][0].record()
         for i, g in enumerate(infl):                                   # a1: publish K/V
             pool.append(g, timesteps[i], 0, k_blocks[i], v_blocks[i])
+        if i_timed is not None:
+            ev_a[i_timed][1].record()
         pool.rope(q, w.frames_per_block * b, out=q_rot)                # a2
         if i_timed is not None:
+            ev_a[i_timed][2].record()
             ev[i_timed][0].record()
         pool.forward(q_rot, infl, mode, out=out)                       # a3-a6
         if i_timed is not None:
@@ -253,6 +260,15 @@ def main() -> int:
                      "traffic": ATTN_TRAFFIC_BYTES_C4 if (w.name == "c4_wan14b_cascade5" and
                                                           mode == B.CA_BIDIRECTIONAL) else None},
     }
+    # the two HBM-bound steps: every element read once and written once
+    eb = 2 if w.dtype == "bf16" else 4
+    append_ms = sum(e[0].elapsed_time(e[1]) for e in ev_a) / args.steps / C
+    rope_ms = sum(e[1].elapsed_time(e[2]) for e in ev_a) / args.steps
+    append_gbs = 2 * (2 * L * H * D * eb) / (append_ms * 1e-3) / 1e9
+    rope_gbs = 2 * (C * L * H * D * eb) / (rope_ms * 1e-3) / 1e9
+    result["secondary"] = {
+        "kv_cache_append": {"us_per_block": append_ms * 1e3, "GB/s": append_gbs, "frac_of_hbm_peak": append_gbs / PEAK_HBM_GBS},
+        "rope3d_apply": {"us": rope_ms * 1e3, "GB/s": rope_gbs, "frac_of_hbm_peak": rope_gbs / PEAK_HBM_GBS}}
     # what the matrix pipes sustain on this machine with nothing else in the loop (the nominal peak
     # assumes 2.4 GHz; under a full MFMA load with toggling operands the chip clocks lower)
     probe = torch.empty(1 << 16, dtype=torch.uint8, device=dev)
