@@ -176,7 +176,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
         "=&{v150}"(l1a), "=&{v151}"(l1b), "=&{v184}"(negm0), "=&{v200}"(negm1)
       : "{a[128:143]}"(qt[0]), "{a[144:159]}"(qt[1]), "{a[160:175]}"(qt[2]), "{a[176:191]}"(qt[3]),
         [xo0] "v"(xo0), [lane_off] "v"(lane_off), [tbl_lo] "v"(tbl_lo), [tbl_hi] "v"(tbl_hi),
-        [kidx] "v"(kidx), [xlane] "v"(xlane), [pool] "s"(a.pool), [n_pages] "s"(n_pages), [n_kvb] "s"(n_kvb), [kb0] "s"(kb0), [pg0] "s"(pg0),
+        [kidx] "v"(kidx), [xlane] "v"(xlane), [n_pages] "s"(n_pages), [n_kvb] "s"(n_kvb), [kb0] "s"(kb0), [pg0] "s"(pg0),
         [ppb] "s"(a.pages_per_block), [stride] "s"(stride), [last_valid] "s"(a.last_valid),
         [wave] "s"(wave_s), [lds0] "s"(lds0)
       : "memory", "vcc", "scc", "m0", CA_CORE_CLOBBERS);

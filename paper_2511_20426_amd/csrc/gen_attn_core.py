@@ -91,14 +91,12 @@ DMAOFF = 216         # 216..223: lane's byte offset in a page for load i (+4096 
 
 # scalar registers (all inside the clobbered range s36..s95)
 S_NLEFT, S_P, S_PM1, S_STRIDE, S_NKVB = 41, 42, 43, 44, 45
-S_POOL = 46          # 46,47
 S_M0B, S_LASTV = 48, 49
 S_VLAST = 50         # 50..53
 S_PGCUR, S_PGNEXT = 54, 55
-S_KKB, S_KPG, S_VKB, S_VPG = 56, 57, 58, 59
+S_KKB, S_KPG = 56, 57  # page cursor: visible KV block, page in it
 S_T = 60             # 60..69 temporaries
 S_ADDR = 70          # 70,71
-S_VCC = 72           # 72,73
 S_LDS0 = 74
 S_ADDRV = 76         # 76,77
 S_RG = 78            # 78,79: nonzero if the tile just produced needs its tail masked
@@ -220,56 +218,19 @@ def emit_mask(E, s_base, valid_sreg):
             E.e(f"v_cndmask_b32 {r}, {V(RT[0])}, {r}, vcc")
 
 
-def emit_settle(E, s_base, p_wait_base, first=False):
-    """Reference update for the S tile at s_base (its maximum, relative to the current m_ref, is in
-    MX): if some score exceeds m_ref by more than the slack, m_ref moves up to the row maximum and
-    everything formed against the old reference is rescaled: row sums, accumulators, the P tile
-    still waiting for its PV product, and this S tile itself.  first=True: unconditional (tile 0)."""
-    cold, back = E.label("RARE"), E.label("BACK")
-    if first:
-        E.e(f"s_branch {cold}")
-    else:
-        E.e(f"v_cmp_lt_f32 vcc, 0x41000000, {V(MX[0])}")           # 8.0 < max
-        E.e(f"s_mov_b64 s[{S_VCC}:{S_VCC + 1}], vcc")
-        E.e(f"v_cmp_lt_f32 vcc, 0x41000000, {V(MX[1])}")
-        E.e(f"s_or_b64 vcc, vcc, s[{S_VCC}:{S_VCC + 1}]")
-        E.e(f"s_cbranch_vccnz {cold}")
-    E.e(f"{back}:")
-    c = E.cold
-    c.append(f"{cold}:")
-    c.append("s_nop 15\ns_nop 15\ns_nop 15")            # every MFMA issued so far has written back
+def emit_first_reference(E, s_base):
+    """The exponent reference of a row starts as the maximum of its first tile (at s_base, its
+    per-lane maxima in MX): the tile and the -m_ref operand move by it.  Nothing has been
+    accumulated yet, so there is nothing to rescale."""
+    E.e("s_nop 15\ns_nop 15\ns_nop 15")                   # every MFMA issued so far has written back
     for nt in range(2):
-        t, other, delta, alpha = V(MX[nt]), V(RT[3]), V(RT[4]), V(RT[6])
-        c.append(f"ds_bpermute_b32 {other}, {V(XLANE)}, {t}")        # the partner lane's (lane ^ 32) maximum
-        c.append("s_waitcnt lgkmcnt(0)")
-        c.append(f"v_max_f32 {delta}, {t}, {other}")
-        if not first:
-            c.append(f"v_max_f32 {delta}, 0, {delta}")               # the reference never moves down
-        c.append(f"v_exp_f32_e64 {alpha}, -{delta}")
-        c.append("s_nop 3")                              # a trans result is not forwarded to the next VALU op
-        for k in range(2):
-            c.append(f"v_mul_f32 {V(LACC + 2 * nt + k)}, {V(LACC + 2 * nt + k)}, {alpha}")
-        for mt in range(4):
-            for i in range(16):
-                acc = A(16 * (2 * mt + nt) + i)
-                tmp = V(RT[8 + (i % 8)])
-                c.append(f"v_accvgpr_read_b32 {tmp}, {acc}")
-                c.append(f"v_mul_f32 {tmp}, {tmp}, {alpha}")
-                c.append(f"v_accvgpr_write_b32 {acc}, {tmp}")
-        for kk in range(2):
-            for w in range(4):
-                r = V(p_wait_base + 4 * (2 * nt + kk) + w)
-                lo, hi = V(RT[8]), V(RT[9])
-                c.append(f"v_lshlrev_b32 {lo}, 16, {r}")
-                c.append(f"v_and_b32 {hi}, 0xffff0000, {r}")
-                c.append(f"v_mul_f32 {lo}, {lo}, {alpha}")
-                c.append(f"v_mul_f32 {hi}, {hi}, {alpha}")
-                c.append(f"v_cvt_pk_bf16_f32 {r}, {lo}, {hi}")
-        for i in range(16):                              # -m_ref operand and the tile itself
-            c.append(f"v_sub_f32 {V(NT[nt] + i)}, {V(NT[nt] + i)}, {delta}")
-            c.append(f"v_sub_f32 {V(s_base + 16 * nt + i)}, {V(s_base + 16 * nt + i)}, {delta}")
-    c.append("s_nop 7")
-    c.append(f"s_branch {back}")
+        t, other, delta = V(MX[nt]), V(RT[3]), V(RT[4])
+        E.e(f"ds_bpermute_b32 {other}, {V(XLANE)}, {t}")             # the partner lane's (lane ^ 32) maximum
+        E.e("s_waitcnt lgkmcnt(0)")
+        E.e(f"v_max_f32 {delta}, {t}, {other}")
+        for i in range(16):
+            E.e(f"v_sub_f32 {V(NT[nt] + i)}, {V(NT[nt] + i)}, {delta}")
+            E.e(f"v_sub_f32 {V(s_base + 16 * nt + i)}, {V(s_base + 16 * nt + i)}, {delta}")
 
 
 def emit_mask_check(E, s_base, pg_sreg, sub):
@@ -525,7 +486,6 @@ def generate():
     E.e(f"s_sub_u32 s{S_PM1}, s{S_P}, 1")
     E.e(f"s_mov_b32 s{S_STRIDE}, %[stride]")
     E.e(f"s_mov_b32 s{S_NKVB}, %[n_kvb]")
-    E.e(f"s_mov_b64 s[{S_POOL}:{S_POOL + 1}], %[pool]")
     E.e(f"s_mov_b32 s{S_LDS0}, %[lds0]")
     E.e(f"s_lshl_b32 s{S_M0B}, %[wave], 10")
     E.e(f"s_add_u32 s{S_M0B}, s{S_M0B}, s{S_LDS0}")
@@ -589,7 +549,7 @@ def generate():
     for op in tile_max_ops(S_TILE["A"]):
         E.e(op)
     emit_mask_check(E, S_TILE["A"], S_PGCUR, 0)
-    emit_settle(E, S_TILE["A"], P_TILE["B"], first=True)
+    emit_first_reference(E, S_TILE["A"])
     # first operand fragments of step (R=0, parity 0)
     for f in range(D_AHEAD):
         E.e(ds_read_frag(f, frag_source(0, 0, f)))
