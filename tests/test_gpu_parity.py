@@ -210,6 +210,25 @@ def test_bf16_every_ragged_tail_class(gh, gw):
         Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", f"ragged L={w.block_tokens} mode={mode}")
 
 
+@pytest.mark.parametrize("case", range(12))
+def test_bf16_seeded_random_shapes(case):
+    """Twelve seeded draws of the shape itself: heads, frames per block, grid, cache depth, blocks
+    in flight, first block id and mode, each case small enough for a full comparison."""
+    rng = np.random.default_rng([2024, case])
+    fpb = int(rng.integers(1, 4))
+    gh, gw = int(rng.integers(2, 17)), int(rng.integers(2, 21))
+    nc, ni = int(rng.integers(0, 4)), int(rng.integers(1, 6))
+    heads = int(rng.integers(1, 5))
+    mode = BI if rng.integers(0, 2) == 0 else CA
+    first = int(rng.integers(0, 6))
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=heads, grid_h=gh, grid_w=gw, frames_per_block=fpb,
+                        n_cached=nc, n_inflight=ni)
+    _say(f"random shape {case}: heads={heads} frames={fpb} grid={gh}x{gw} L={w.block_tokens} cached={nc} "
+         f"inflight={ni} first={first} mode={mode}")
+    outs, ref = _one_shot(w, mode, seed=1000 + case, first_block=first)
+    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", f"random shape {case}")
+
+
 def test_bf16_single_block_modes_agree_bitwise():
     """One in-flight block: both modes are the same computation (cascade P1, Fig. 7)."""
     w = W.small_variant(W.CONFIGS["c2_wan1p3b_seq"], heads=2, grid_h=9, grid_w=14, n_cached=3)
