@@ -134,6 +134,13 @@ int32_t rope3d_apply(const ca_ctx* ctx, const void* x_dev, void* y_dev, int64_t 
                      int64_t first_frame, int64_t tok_stride, int64_t head_stride,
                      void* hip_stream);
 
+/* The same with strides of its own for the output (elements; the two views must not overlap
+ * unless they are identical): e.g. q out of a packed [tokens][3][heads][head_dim] projection
+ * result straight into the contiguous tensor cascade_attn_forward takes. */
+int32_t rope3d_apply_strided(const ca_ctx* ctx, const void* x_dev, int64_t x_tok_stride, int64_t x_head_stride,
+                             void* y_dev, int64_t y_tok_stride, int64_t y_head_stride, int64_t n_tokens,
+                             int64_t first_frame, void* hip_stream);
+
 /* Block-cascaded attention.  q_dev / out_dev: [n_inflight*L, heads, head_dim] contiguous,
  * rotated queries of the in-flight blocks in the order of inflight_block_ids, which must be
  * strictly ascending, resident and NOISY (their K/V appended for this step).

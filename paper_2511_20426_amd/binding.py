@@ -26,7 +26,7 @@ CA_FREE, CA_NOISY, CA_CLEAN, CA_SINK = 0, 1, 2, 3
 EXPORTS = (
     "ca_pool_bytes", "ca_create", "ca_destroy", "kv_cache_append", "kv_cache_promote",
     "kv_cache_evict", "kv_cache_retag", "kv_cache_snapshot", "kv_cache_page_index",
-    "rope3d_apply", "cascade_attn_forward", "ca_debug_visibility", "ca_set_kernel_variant",
+    "rope3d_apply", "rope3d_apply_strided", "cascade_attn_forward", "ca_debug_visibility", "ca_set_kernel_variant",
     "ca_strerror", "ca_last_device_error",
     "ca_mfma_microbench", "layer_linear_bf16",
     "ca_sched_create", "ca_sched_create_lagged", "ca_sched_destroy", "ca_sched_batch", "ca_sched_advance", "ca_sched_state",
@@ -90,6 +90,8 @@ def _load() -> C.CDLL:
     lib.kv_cache_page_index.argtypes = [vp, i64, i32, i32, C.POINTER(i64)]
     lib.rope3d_apply.restype = i32
     lib.rope3d_apply.argtypes = [vp, vp, vp, i64, i64, i64, i64, vp]
+    lib.rope3d_apply_strided.restype = i32
+    lib.rope3d_apply_strided.argtypes = [vp, vp, i64, i64, vp, i64, i64, i64, i64, vp]
     lib.cascade_attn_forward.restype = i32
     lib.cascade_attn_forward.argtypes = [vp, vp, C.POINTER(i64), i32, i32, vp, vp]
     lib.ca_debug_visibility.restype = i32
@@ -213,6 +215,13 @@ class Context:
         _check(lib.rope3d_apply(self._h, C.c_void_p(x_ptr or None), C.c_void_p(y_ptr or None), n_tokens,
                                 first_frame, tok_stride, head_stride, C.c_void_p(stream or None)),
                "rope3d_apply")
+
+    def rope3d_apply_strided(self, x_ptr: int, x_tok_stride: int, x_head_stride: int, y_ptr: int,
+                             y_tok_stride: int, y_head_stride: int, n_tokens: int, first_frame: int,
+                             stream: int = 0) -> None:
+        _check(lib.rope3d_apply_strided(self._h, C.c_void_p(x_ptr or None), x_tok_stride, x_head_stride,
+                                        C.c_void_p(y_ptr or None), y_tok_stride, y_head_stride, n_tokens,
+                                        first_frame, C.c_void_p(stream or None)), "rope3d_apply_strided")
 
     def cascade_attn_forward(self, q_ptr: int, inflight_block_ids: Sequence[int], mode: int, out_ptr: int,
                              stream: int = 0) -> None:

@@ -117,19 +117,26 @@ int32_t kv_cache_page_index(const ca_ctx* ctx, int64_t block_id, int32_t page, i
   return CA_OK;
 }
 
-int32_t rope3d_apply(const ca_ctx* ctx, const void* x_dev, void* y_dev, int64_t n_tokens,
-                     int64_t first_frame, int64_t tok_stride, int64_t head_stride,
-                     void* hip_stream) {
+int32_t rope3d_apply_strided(const ca_ctx* ctx, const void* x_dev, int64_t x_tok_stride, int64_t x_head_stride,
+                             void* y_dev, int64_t y_tok_stride, int64_t y_head_stride, int64_t n_tokens,
+                             int64_t first_frame, void* hip_stream) {
   if (!ctx || n_tokens < 0 || first_frame < 0) return CA_EINVAL;
   if (!ctx->pool) return CA_ENOPOOL;
   if (n_tokens == 0) return CA_OK;
   if (!x_dev || !y_dev) return CA_EINVAL;
   const ca::CacheMeta& m = ctx->meta;
-  if (!strides_ok(m.cfg(), x_dev, tok_stride, head_stride) ||
-      !strides_ok(m.cfg(), y_dev, tok_stride, head_stride))
+  if (!strides_ok(m.cfg(), x_dev, x_tok_stride, x_head_stride) ||
+      !strides_ok(m.cfg(), y_dev, y_tok_stride, y_head_stride))
     return CA_EINVAL;
   return ca::launch_rope_apply(rope_geom(m), m.cfg().dtype, x_dev, y_dev, n_tokens, first_frame,
-                               tok_stride, head_stride, hip_stream);
+                               x_tok_stride, x_head_stride, y_tok_stride, y_head_stride, hip_stream);
+}
+
+int32_t rope3d_apply(const ca_ctx* ctx, const void* x_dev, void* y_dev, int64_t n_tokens,
+                     int64_t first_frame, int64_t tok_stride, int64_t head_stride,
+                     void* hip_stream) {
+  return rope3d_apply_strided(ctx, x_dev, tok_stride, head_stride, y_dev, tok_stride, head_stride, n_tokens,
+                              first_frame, hip_stream);
 }
 
 int32_t cascade_attn_forward(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,

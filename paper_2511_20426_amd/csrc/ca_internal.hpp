@@ -73,7 +73,7 @@ struct RopeGeom {
 // y = rope(x) on [n_tokens, heads, head_dim]; token n sits at frame first_frame + n/(gh*gw).
 int32_t launch_rope_apply(const RopeGeom& g, int dtype, const void* x, void* y, int64_t n_tokens,
                           int64_t first_frame, int64_t tok_stride, int64_t head_stride,
-                          void* stream);
+                          int64_t y_tok_stride, int64_t y_head_stride, void* stream);
 
 // Fused K-rotation + K/V page store of one block into its slot.
 int32_t launch_cache_write(const RopeGeom& g, int dtype, const void* k, const void* v,

@@ -110,6 +110,7 @@ struct GenericArgs {
   const void* v;        // MODE 1: V
   void* y;              // MODE 0: output; MODE 1: pool
   int64_t n_tokens, first_frame, tok_stride, head_stride;
+  int64_t y_tok_stride, y_head_stride;   // MODE 0: strides of the output
   int32_t heads_per_group;
   // MODE 1 only: n_tokens covers whole pages, tokens >= valid_tokens are stored as zeros
   int32_t page_tokens, pages_per_block, slot, valid_tokens;
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(256) void rope_generic_kernel(RopeGeom g, GenericAr
       rotate8(e, cs, sn);
     }
     if (MODE == 0) {
-      e.store(static_cast<T*>(a.y) + src);
+      e.store(static_cast<T*>(a.y) + n * a.y_tok_stride + int64_t(h) * a.y_head_stride + c8 * 8);
     } else {
       const int64_t page = n / a.page_tokens, row = n % a.page_tokens;
       const int64_t page_elems = int64_t(a.page_tokens) * g.head_dim;
@@ -336,12 +337,13 @@ int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot) {
 
 int32_t launch_rope_apply(const RopeGeom& g, int dtype, const void* x, void* y, int64_t n_tokens,
                           int64_t first_frame, int64_t tok_stride, int64_t head_stride,
-                          void* stream) {
+                          int64_t y_tok_stride, int64_t y_head_stride, void* stream) {
   if (n_tokens == 0) return CA_OK;
   GenericArgs a{};
   a.x = x; a.v = nullptr; a.y = y;
   a.n_tokens = n_tokens; a.first_frame = first_frame;
   a.tok_stride = tok_stride; a.head_stride = head_stride;
+  a.y_tok_stride = y_tok_stride; a.y_head_stride = y_head_stride;
   const int64_t gx = (n_tokens + 3) / 4;           // one wave per token, four per workgroup
   if (gx > 0x7fffffff) return CA_EINVAL;
   // enough workgroups to fill 256 CUs several times over, few enough to amortise the trig

@@ -71,9 +71,8 @@ class CascadeRollout:
         from .runner import torch_dtype
         dt = torch_dtype(self.pool.dtype)
         n = len(self.timesteps)
-        self._q = torch.empty((n * L, H, D), dtype=dt, device=self.pool.device)
-        self._qr = torch.empty_like(self._q)
-        self._o = torch.empty_like(self._q)
+        self._qr = torch.empty((n * L, H, D), dtype=dt, device=self.pool.device)
+        self._o = torch.empty_like(self._qr)
 
     def step(self) -> Optional[IterationRecord]:
         """One iteration of Alg. 1; None once the rollout is over."""
@@ -93,10 +92,10 @@ class CascadeRollout:
         n = len(batch)
         for i, ((g, ti, t), (q, k, v)) in enumerate(zip(batch, staged)):
             pool.append(g, t, self.epoch, k, v)
-            self._q[i * L:(i + 1) * L].copy_(q)
+            # each block's queries are rotated from wherever they live into the packed tensor
+            pool.rope(q, pool.frames_per_block * g, out=self._qr[i * L:(i + 1) * L])
         infl = [g for g, _, _ in batch]
-        qr = pool.rope(self._q[:n * L], pool.frames_per_block * infl[0], out=self._qr[:n * L])
-        o = pool.forward(qr, infl, self.mode, out=self._o[:n * L])
+        o = pool.forward(self._qr[:n * L], infl, self.mode, out=self._o[:n * L])
         if self.post_fn is not None:
             self.post_fn(o)
         emitted, completed = self.sched.advance()

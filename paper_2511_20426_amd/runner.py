@@ -59,14 +59,14 @@ class CascadePool:
                                         k.stride(0), k.stride(1), self._stream())
 
     def rope(self, x: torch.Tensor, first_frame: int, out: torch.Tensor | None = None) -> torch.Tensor:
+        """Rotate x [n, H, D] (any token / head strides) into `out` (its own strides; default: a new
+        contiguous tensor).  x is out is allowed."""
         self._check(x)
-        if out is None:
-            assert x.is_contiguous(), "pass `out` with the strides of a non-contiguous input"
-            out = torch.empty_like(x)
-        y = out
-        assert y.stride() == x.stride() and y.shape == x.shape
-        self.ctx.rope3d_apply(x.data_ptr(), y.data_ptr(), x.shape[0], first_frame, x.stride(0),
-                              x.stride(1), self._stream())
+        y = torch.empty(x.shape, dtype=x.dtype, device=x.device) if out is None else out
+        self._check(y)
+        assert y.shape == x.shape
+        self.ctx.rope3d_apply_strided(x.data_ptr(), x.stride(0), x.stride(1), y.data_ptr(), y.stride(0), y.stride(1),
+                                      x.shape[0], first_frame, self._stream())
         return y
 
     def forward(self, q_rot: torch.Tensor, inflight: Sequence[int], mode: int,
@@ -104,9 +104,6 @@ def attention_layer(pool: CascadePool, x: torch.Tensor, w_qkv: torch.Tensor, w_o
     qkv = linear(x, w_qkv).view(n, 3, H, D)
     for i, (g, t) in enumerate(zip(inflight, timesteps)):
         pool.append(g, t, epoch, qkv[i * L:(i + 1) * L, 1], qkv[i * L:(i + 1) * L, 2])
-    q_rot = torch.empty((n, H, D), dtype=x.dtype, device=x.device)
-    # rope3d_apply wants equal strides for input and output: rotate in place in the view, then pack
-    pool.rope(qkv[:, 0], pool.frames_per_block * inflight[0], out=qkv[:, 0])
-    q_rot.copy_(qkv[:, 0])
+    q_rot = pool.rope(qkv[:, 0], pool.frames_per_block * inflight[0])     # strided view -> contiguous
     o = pool.forward(q_rot, inflight, mode)
     return linear(o.view(n, H * D), w_out)

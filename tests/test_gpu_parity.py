@@ -96,6 +96,16 @@ def test_rope3d_apply_matches_oracle(name):
     pool.rope(z, first_frame, out=z)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(Hn.from_torch(z, w.dtype), got)
+    # and so does a strided input rotated straight into a contiguous output, and into a view
+    # with head and token strides of its own (rope3d_apply_strided)
+    packed = pool.rope(view, first_frame)
+    assert packed.is_contiguous()
+    wide = torch.zeros((n, H + 2, D + 8), dtype=xt.dtype, device=xt.device)
+    pool.rope(view, first_frame, out=wide[:, 1:H + 1, :D])
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(Hn.from_torch(packed, w.dtype), got)
+    np.testing.assert_array_equal(Hn.from_torch(wide[:, 1:H + 1, :D].contiguous(), w.dtype), got)
+    assert not wide[:, 0].any() and not wide[:, H + 1].any() and not wide[:, :, D:].any()
 
 
 @pytest.mark.parametrize("name", ["c1_tiny_f32", "c3_small"])
