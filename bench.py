@@ -142,6 +142,11 @@ def main() -> int:
                     help="blocks in flight (cascade types P1..P4 of Fig. 7: 1, 2, 3, 5); default: the workload's")
     ap.add_argument("--cached", type=int, default=None,
                     help="clean cached blocks (2 = the paper's 7-block window accounting); default: the workload's")
+    ap.add_argument("--share", type=int, default=None,
+                    help="time one device's share of the step under the paper's temporal parallelism (one "
+                         "in-flight block per GPU, every GPU holding the whole pool): only the queries of "
+                         "in-flight block SHARE (0 = oldest) are rotated and attended; the five appends stand "
+                         "in for the K/V exchange")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead (known traffic, for scaling rocprofv3's "
@@ -193,6 +198,9 @@ def main() -> int:
     def draw(n):
         return (torch.randn((n, H, D), generator=gen, device=dev, dtype=torch.float32) * w.input_scale).to(dt)
 
+    if args.share is not None and not 0 <= args.share < C:
+        print("--share must be in 0..%d" % (C - 1), file=sys.stderr)
+        return 2
     q = draw(C * L)
     k_blocks = [draw(L) for _ in range(C)]
     v_blocks = [draw(L) for _ in range(C)]
@@ -218,11 +226,17 @@ def main() -> int:
             pool.append(g, timesteps[i], 0, k_blocks[i], v_blocks[i])
         if i_timed is not None:
             ev_a[i_timed][1].record()
-        pool.rope(q, w.frames_per_block * b, out=q_rot)                # a2
+        if args.share is None:
+            pool.rope(q, w.frames_per_block * b, out=q_rot)            # a2
+        else:
+            pool.rope(q[:L], w.frames_per_block * (b + args.share), out=q_rot[:L])
         if i_timed is not None:
             ev_a[i_timed][2].record()
             ev[i_timed][0].record()
-        pool.forward(q_rot, infl, mode, out=out)                       # a3-a6
+        if args.share is None:
+            pool.forward(q_rot, infl, mode, out=out)                   # a3-a6
+        else:
+            pool.forward(q_rot[:L], infl, mode, out=out[:L], share=(args.share, 1))
         if i_timed is not None:
             ev[i_timed][1].record()
         pool.ctx.kv_cache_promote(b)                                   # a7
@@ -239,11 +253,17 @@ def main() -> int:
     dt_s = time.perf_counter() - t0
 
     flops = w.flops(block_causal=(mode == B.CA_BLOCK_CAUSAL))
+    n_rot = C
+    if args.share is not None:
+        vis_blocks = w.n_cached + (args.share + 1 if mode == B.CA_BLOCK_CAUSAL else C)
+        flops = 4.0 * D * L * vis_blocks * L * H
+        n_rot = 1
     ms_per_step = dt_s / args.steps * 1e3
     attn_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
     achieved = flops / (attn_ms * 1e-3) / 1e12
     result = {
-        "metric": "cascaded-attn TFLOP/s + % bf16 MFMA peak, Wan-14B shape, 5 in-flight blocks",
+        "metric": "cascaded-attn TFLOP/s + % bf16 MFMA peak, Wan-14B shape, 5 in-flight blocks" +
+                  ("" if args.share is None else ", one device's share (queries of in-flight block %d)" % args.share),
         "value": flops / (ms_per_step * 1e-3) / 1e12,
         "unit": "TFLOP/s",
         "pct_of_bf16_mfma_peak": 100.0 * flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
@@ -252,20 +272,22 @@ def main() -> int:
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "heads": H, "head_dim": D, "tokens_per_block": L,
                    "inflight_blocks": C, "cached_blocks": w.n_cached, "mode": args.mode,
-                   "n_q": C * L, "n_kv": (w.n_cached + C) * L, "flops_per_step": flops,
-                   "step": "%dx kv_cache_append + rope3d_apply(Q) + cascade_attn_forward + promote/evict" % C},
+                   "n_q": n_rot * L, "n_kv": (w.n_cached + C) * L, "flops_per_step": flops,
+                   "step": "%dx kv_cache_append + rope3d_apply(Q) + %s + promote/evict"
+                           % (C, "cascade_attn_forward" if args.share is None else "cascade_attn_forward_share")},
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "avg_launch_ms": attn_ms,
                      "traffic": ATTN_TRAFFIC_BYTES_C4 if (w.name == "c4_wan14b_cascade5" and
-                                                          mode == B.CA_BIDIRECTIONAL) else None},
+                                                          mode == B.CA_BIDIRECTIONAL and
+                                                          args.share is None) else None},
     }
     # the two HBM-bound steps: every element read once and written once
     eb = 2 if w.dtype == "bf16" else 4
     append_ms = sum(e[0].elapsed_time(e[1]) for e in ev_a) / args.steps / C
     rope_ms = sum(e[1].elapsed_time(e[2]) for e in ev_a) / args.steps
     append_gbs = 2 * (2 * L * H * D * eb) / (append_ms * 1e-3) / 1e9
-    rope_gbs = 2 * (C * L * H * D * eb) / (rope_ms * 1e-3) / 1e9
+    rope_gbs = 2 * (n_rot * L * H * D * eb) / (rope_ms * 1e-3) / 1e9
     result["secondary"] = {
         "kv_cache_append": {"us_per_block": append_ms * 1e3, "GB/s": append_gbs, "frac_of_hbm_peak": append_gbs / PEAK_HBM_GBS},
         "rope3d_apply": {"us": rope_ms * 1e3, "GB/s": rope_gbs, "frac_of_hbm_peak": rope_gbs / PEAK_HBM_GBS}}

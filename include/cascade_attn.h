@@ -152,6 +152,19 @@ int32_t cascade_attn_forward(ca_ctx* ctx, const void* q_dev,
                              const int64_t* inflight_block_ids, int32_t n_inflight,
                              int32_t mode, void* out_dev, void* hip_stream);
 
+/* One device's share of the same forward when the in-flight blocks are spread over several
+ * GPUs, one block per GPU, all of which hold the whole pool (temporal parallelism, Sec. 3.3 /
+ * 3.4: every GPU denoises its own block and reads the others' K/V).  Arguments and KV sequence
+ * as for cascade_attn_forward; only the queries of in-flight blocks first .. first+count-1 (an
+ * index range into inflight_block_ids) are computed: q_dev / out_dev hold just those blocks,
+ * [count*L, heads, head_dim] contiguous.  Each of those rows gets the result the whole forward
+ * gives it up to floating-point summation order.  first < 0, count < 1 or a range past
+ * n_inflight is CA_EINVAL. */
+int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev,
+                                   const int64_t* inflight_block_ids, int32_t n_inflight,
+                                   int32_t first, int32_t count, int32_t mode, void* out_dev,
+                                   void* hip_stream);
+
 /* The mask cascade_attn_forward would use: vis[i*n_kv + r] in {0,1} for query block i and
  * KV block r of the KV sequence, kv_block_ids[r] its block id.  cap = capacity of
  * kv_block_ids (and vis holds n_inflight*cap bytes); n_kv_out gets the sequence length. */

@@ -141,11 +141,19 @@ int32_t rope3d_apply(const ca_ctx* ctx, const void* x_dev, void* y_dev, int64_t 
 
 int32_t cascade_attn_forward(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,
                              int32_t n_inflight, int32_t mode, void* out_dev, void* hip_stream) {
+  return cascade_attn_forward_share(ctx, q_dev, inflight_block_ids, n_inflight, 0, n_inflight, mode, out_dev,
+                                    hip_stream);
+}
+
+int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,
+                                   int32_t n_inflight, int32_t first, int32_t count, int32_t mode,
+                                   void* out_dev, void* hip_stream) {
   if (!ctx) return CA_EINVAL;
   const ca::CacheMeta& m = ctx->meta;
   std::vector<int64_t> ids;
   std::vector<int32_t> slots, n_vis;
   if (int32_t rc = m.plan_forward(inflight_block_ids, n_inflight, mode, &ids, &slots, &n_vis)) return rc;
+  if (first < 0 || count < 1 || first > n_inflight - count) return CA_EINVAL;
   if (!ctx->pool) return CA_ENOPOOL;
   if (!q_dev || !out_dev) return CA_EINVAL;
   if ((reinterpret_cast<uintptr_t>(q_dev) | reinterpret_cast<uintptr_t>(out_dev)) & 15) return CA_EINVAL;
@@ -156,13 +164,13 @@ int32_t cascade_attn_forward(ca_ctx* ctx, const void* q_dev, const int64_t* infl
   p.page_tokens = c.page_tokens;
   p.pages_per_block = m.pages_per_block();
   p.block_tokens = m.block_tokens();
-  p.n_q_blocks = n_inflight;
+  p.n_q_blocks = count;
   p.n_kv = int32_t(ids.size());
   p.uniform = 1;
   for (int i = 0; i < p.n_kv; ++i) p.kv_slot[i] = slots[i];
-  for (int i = 0; i < n_inflight; ++i) {
-    p.n_vis[i] = n_vis[i];
-    if (n_vis[i] != p.n_kv) p.uniform = 0;
+  for (int i = 0; i < count; ++i) {
+    p.n_vis[i] = n_vis[first + i];
+    if (p.n_vis[i] != p.n_vis[0]) p.uniform = 0;
   }
   if (c.dtype == CA_BF16)
     return ca::launch_attn_bf16(p, ctx->variant, q_dev, out_dev, ctx->pool,

@@ -83,11 +83,11 @@ int32_t launch_cache_write(const RopeGeom& g, int dtype, const void* k, const vo
 
 struct AttnPlan {
   int32_t heads, head_dim, page_tokens, pages_per_block, block_tokens;
-  int32_t n_q_blocks;                 // in-flight blocks; query rows are n_q_blocks * block_tokens
+  int32_t n_q_blocks;                 // query blocks of this launch; query rows are n_q_blocks * block_tokens
   int32_t n_kv;                       // length of the KV sequence
   int32_t kv_slot[kMaxKvBlocks];
   int32_t n_vis[kMaxInflight];        // visible prefix length per query block
-  int32_t uniform;                    // every query block sees the whole sequence
+  int32_t uniform;                    // every query block sees the same prefix, n_vis[0]
 };
 
 int32_t launch_attn_f32(const AttnPlan& p, const void* q, void* out, const void* pool, void* stream);

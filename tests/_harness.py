@@ -101,6 +101,18 @@ def gpu_forward(w: W.Workload, pool, q, inflight_g, mode):
     return from_torch(out, w.dtype)
 
 
+def gpu_forward_share(w: W.Workload, pool, q, inflight_g, mode, first, count):
+    """The same for the queries of in-flight blocks first .. first+count-1 only
+    (cascade_attn_forward_share); q is the whole [C*L, H, D] tensor, the result [count*L, H, D]."""
+    import torch
+    L = w.block_tokens
+    qt = to_torch(np.ascontiguousarray(q[first * L:(first + count) * L]), w.dtype)
+    qr = pool.rope(qt, w.frames_per_block * inflight_g[first])
+    out = pool.forward(qr, inflight_g, mode, share=(first, count))
+    torch.cuda.synchronize()
+    return from_torch(out, w.dtype)
+
+
 # --------------------------------------------------------------------------- pool decoding
 # Written from the page format documented in include/cascade_attn.h.
 

@@ -239,6 +239,35 @@ def test_bf16_seeded_random_shapes(case):
     Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", f"random shape {case}")
 
 
+@pytest.mark.parametrize("mode", [BI, CA])
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_share_of_a_forward_every_block_range(mode, dtype):
+    """cascade_attn_forward_share for every range of in-flight blocks: each row against the
+    oracle's result for that row in the whole cascade, and against the whole forward."""
+    if dtype == "bf16":
+        w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=9, grid_w=13, n_cached=2, n_inflight=4)
+    else:
+        w = W.small_variant(W.CONFIGS["c1_tiny_f32"], heads=2, grid_h=5, grid_w=7, n_cached=1, n_inflight=4,
+                            max_inflight=4)
+    _say(f"share dtype={dtype} mode={mode} tokens/block={w.block_tokens}")
+    q, k, v = W.draw_config(w, seed=33)
+    cached = list(range(3, 3 + w.n_cached))
+    infl = list(range(3 + w.n_cached, 3 + w.n_cached + w.n_inflight))
+    pool = Hn.gpu_setup(w, k, v, cached, infl)
+    whole = W.split_blocks(Hn.gpu_forward(w, pool, q, infl, mode), w.block_tokens)
+    ref = Hn.oracle_forward(w, q, k, v, cached, infl, mode)
+    for first in range(w.n_inflight):
+        for count in range(1, w.n_inflight - first + 1):
+            part = Hn.gpu_forward_share(w, pool, q, infl, mode, first, count)
+            Hn.assert_close(part, np.concatenate(ref[first:first + count]), dtype, f"share ({first},{count})")
+            same = np.concatenate(whole[first:first + count])
+            if dtype == "bf16":
+                keys = (w.n_cached + (first + 1 if mode == CA else w.n_inflight)) * w.block_tokens
+                assert (np.abs(part - same) <= _reordering_bound(part, same, v, keys)).all()
+            else:
+                np.testing.assert_array_equal(part, same)     # one thread per row: tiling cannot matter
+
+
 def test_bf16_single_block_modes_agree_bitwise():
     """One in-flight block: both modes are the same computation (cascade P1, Fig. 7)."""
     w = W.small_variant(W.CONFIGS["c2_wan1p3b_seq"], heads=2, grid_h=9, grid_w=14, n_cached=3)
@@ -284,7 +313,16 @@ def test_bf16_deterministic():
 
 # --------------------------------------------------------------------------- full shapes, sampled rows
 
-def _full_shape(name, modes, heads_sample, n_random):
+def _reordering_bound(a, b, v, keys):
+    """Two GPU results of the same rows that differ only in how the KV walk was cut or tiled:
+    the final bf16 rounding (2 ulps allowed) and the probabilities, which are rounded to bf16
+    against another exponent reference (2^-9 relative per term, i.e. 2^-9 rms(v) / sqrt(keys) on
+    the output; 8 sigma allowed)."""
+    v_rms = float(np.sqrt(np.mean(W.bf16_bits_to_f32(v).astype(np.float64) ** 2)))
+    return 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + 8 * 2.0 ** -9 * v_rms / np.sqrt(keys)
+
+
+def _full_shape(name, modes, heads_sample, n_random, shares=()):
     w = W.CONFIGS[name]
     t0 = time.time()
     q, k, v = W.draw_config(w)
@@ -305,9 +343,7 @@ def _full_shape(name, modes, heads_sample, n_random):
         Hn.assert_close(np.concatenate(got), np.concatenate(ref), "bf16", f"{name} mode={mode}")
         # properties that hold for every row at any size: outputs are convex combinations of V rows,
         # and cutting the KV walk of the last work items into page ranges (tail balancing, merged
-        # afterwards) changes a result only through rounding: of the final bf16 (2 ulps allowed) and of
-        # the probabilities, which are rounded to bf16 against another exponent reference in each
-        # range (2^-9 relative per term, i.e. 2^-9 rms(v) / sqrt(keys) on the output; 8 sigma allowed)
+        # afterwards) changes a result only through rounding
         assert np.isfinite(out).all()
         assert np.abs(out).max() <= np.abs(W.bf16_bits_to_f32(v)).max()
         pool.ctx.set_kernel_variant(1)
@@ -316,14 +352,25 @@ def _full_shape(name, modes, heads_sample, n_random):
         gap = np.abs(out - whole)
         _say(f"{name}: split vs whole KV walks: {int((gap > 0).sum())} of {gap.size} elements differ, "
              f"max {float(gap.max()):.2e}")
-        v_rms = float(np.sqrt(np.mean(W.bf16_bits_to_f32(v).astype(np.float64) ** 2)))
         keys = (w.n_cached + (1 if mode == CA else w.n_inflight)) * L
-        bound = 2.0 ** -7 * np.maximum(np.abs(out), np.abs(whole)) + 8 * 2.0 ** -9 * v_rms / np.sqrt(keys)
-        bad = np.argwhere(gap > bound)
+        bad = np.argwhere(gap > _reordering_bound(out, whole, v, keys))
         if len(bad):
             i = tuple(bad[0])
             _say(f"{name}: {len(bad)} outside the bound, first at {i}: {out[i]!r} vs {whole[i]!r}")
         assert len(bad) == 0
+        # one device's share of the forward (queries of some in-flight blocks only): same rows,
+        # tiled from the share's first row instead of the batch's
+        for first, count in shares:
+            part = Hn.gpu_forward_share(w, pool, q, infl, mode, first, count)
+            ref_rows = out[first * L:(first + count) * L]
+            keys_s = (w.n_cached + (first + 1 if mode == CA else w.n_inflight)) * L
+            gap = np.abs(part - ref_rows)
+            _say(f"{name}: share ({first},{count}) mode={mode} vs whole forward: max {float(gap.max()):.2e}")
+            assert (gap <= _reordering_bound(part, ref_rows, v, keys_s)).all()
+            got = [o[np.asarray(r)][:, list(heads_sample)]
+                   for o, r in zip(W.split_blocks(part, L), rows[first:first + count])]
+            Hn.assert_close(np.concatenate(got), np.concatenate(ref[first:first + count]), "bf16",
+                            f"{name} share ({first},{count}) mode={mode}")
 
 
 def test_c2_wan1p3b_sequential_sampled():
@@ -331,11 +378,11 @@ def test_c2_wan1p3b_sequential_sampled():
 
 
 def test_c3_wan1p3b_cascade_both_modes_sampled():
-    _full_shape("c3_wan1p3b_cascade5", [BI, CA], heads_sample=(0, 5, 11), n_random=12)
+    _full_shape("c3_wan1p3b_cascade5", [BI, CA], heads_sample=(0, 5, 11), n_random=12, shares=((0, 1), (3, 2)))
 
 
 def test_c4_wan14b_cascade_sampled():
-    _full_shape("c4_wan14b_cascade5", [BI], heads_sample=(0, 1, 17, 39), n_random=8)
+    _full_shape("c4_wan14b_cascade5", [BI], heads_sample=(0, 1, 17, 39), n_random=8, shares=((2, 1),))
 
 
 # --------------------------------------------------------------------------- long rollout (ring buffer)

@@ -149,6 +149,12 @@ def test_error_paths_leave_state_unchanged():
     fails(B.CA_EINVAL, ctx.debug_visibility, [], B.CA_BIDIRECTIONAL)
     fails(B.CA_EINVAL, ctx.debug_visibility, [0, 1, 2], B.CA_BIDIRECTIONAL)  # more than max_inflight
     fails(B.CA_ENOPOOL, ctx.rope3d_apply, 0, 0, 10, 0, 128, 128)
+    # one device's share of a forward: the block range is checked before the pool is
+    for first, count in ((-1, 1), (0, 0), (0, 3), (2, 1), (1, 2), (0, -1)):
+        fails(B.CA_EINVAL, ctx.cascade_attn_forward_share, 0, [0, 1], first, count, B.CA_BIDIRECTIONAL, 0)
+    fails(B.CA_ENOENT, ctx.cascade_attn_forward_share, 0, [0, 2], 0, 1, B.CA_BIDIRECTIONAL, 0)
+    for first, count in ((0, 1), (1, 1), (0, 2)):
+        fails(B.CA_ENOPOOL, ctx.cascade_attn_forward_share, 0, [0, 1], first, count, B.CA_BLOCK_CAUSAL, 0)
     fails(B.CA_EINVAL, ctx.set_kernel_variant, 12345)
     ctx.set_kernel_variant(1)
     ctx.set_kernel_variant(0)
