@@ -15,6 +15,10 @@
  *     owns host metadata only.  Device calls are asynchronous on the given stream (a
  *     hipStream_t passed as void*, NULL = the default stream) and never synchronise; device
  *     buffers must stay valid until that work has run.
+ *   - Device calls enqueue kernel launches only (no allocation, no memset, no copy).  The
+ *     first bf16 forward / linear call on a device also sets a kernel attribute; after that
+ *     warm-up the calls can be recorded into a HIP graph.  Host metadata (slot map, tags)
+ *     changes when the call is made, not when a recorded graph replays.
  *   - A context is not thread-safe; calls on one context that overlap on the GPU in
  *     different streams are the caller's to order.
  *   - Tensors are [token, head, dim] with element strides tok_stride / head_stride and unit

@@ -311,6 +311,47 @@ def test_bf16_deterministic():
     np.testing.assert_array_equal(a, b)
 
 
+def test_step_replays_from_a_hip_graph():
+    """Cache write, Q rotation and attention (with split work items, i.e. the merge kernel too)
+    captured into a HIP graph after one eager warm-up call: the library launches plain kernels
+    on the caller's stream, allocates nothing and sets its one-time kernel attributes on the
+    first call.  Every replay, with fresh inputs and eager work in between, must reproduce the
+    eager result bit for bit."""
+    import torch
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=16, grid_h=19, grid_w=27, n_cached=1, n_inflight=3)
+    L = w.block_tokens
+    q, k, v = W.draw_config(w, seed=61)
+    pool = Hn.gpu_setup(w, k, v, [0], [1, 2, 3])
+    qs = Hn.to_torch(q, "bf16")
+    ks, vs = Hn.to_torch(k, "bf16")[3 * L:].clone(), Hn.to_torch(v, "bf16")[3 * L:].clone()
+    q_rot, out = torch.empty_like(qs), torch.empty_like(qs)
+
+    def step():
+        pool.append(3, 1000, 0, ks, vs)                      # the newest block's K/V are rewritten
+        pool.rope(qs, w.frames_per_block * 1, out=q_rot)
+        pool.forward(q_rot, [1, 2, 3], BI, out=out)
+
+    step()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    gen = torch.Generator(device="cuda:0").manual_seed(5)
+    for trial in range(3):
+        for t in (qs, ks, vs):
+            t.copy_((torch.randn(t.shape, generator=gen, device="cuda:0") * 0.5).to(torch.bfloat16))
+        step()
+        torch.cuda.synchronize()
+        expect = out.clone()
+        out.zero_()
+        q_rot.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), expect.view(torch.int16)), f"replay {trial}"
+        assert bool(out.float().abs().max() > 0)
+
+
 # --------------------------------------------------------------------------- full shapes, sampled rows
 
 def _reordering_bound(a, b, v, keys):
