@@ -42,7 +42,7 @@ class CascadePool:
     def for_workload(cls, w, device="cuda:0"):
         return cls(heads=w.heads, head_dim=w.head_dim, frames_per_block=w.frames_per_block,
                    grid_h=w.grid_h, grid_w=w.grid_w, rope_dims=w.rope_dims, rope_theta=w.rope_theta,
-                   sink_blocks=w.sink_blocks, window_blocks=max(w.window_blocks, w.n_cached),
+                   sink_blocks=w.sink_blocks, window_blocks=max(w.window_blocks, w.n_cached - w.sink_blocks),
                    max_inflight=w.max_inflight, page_tokens=w.page_tokens, dtype=w.dtype, device=device)
 
     def _stream(self) -> int:

@@ -268,6 +268,18 @@ def test_share_of_a_forward_every_block_range(mode, dtype):
                 np.testing.assert_array_equal(part, same)     # one thread per row: tiling cannot matter
 
 
+@pytest.mark.parametrize("mode", [BI, CA])
+@pytest.mark.parametrize("gh,gw", [(4, 5), (6, 9)])
+def test_bf16_largest_configuration(mode, gh, gw):
+    """The limits of a context: 32 KV blocks (1 sink + 23 clean + 8 in flight) and 8 query
+    segments in block-causal mode, on a small token grid."""
+    w = W.small_variant(W.CONFIGS["c5_wan1p3b_rollout"], heads=2, grid_h=gh, grid_w=gw, window_blocks=23,
+                        max_inflight=8, n_cached=24, n_inflight=8)
+    _say(f"largest configuration grid={gh}x{gw} mode={mode}")
+    outs, ref = _one_shot(w, mode, seed=71)
+    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", "32 KV blocks, 8 in flight")
+
+
 def test_bf16_single_block_modes_agree_bitwise():
     """One in-flight block: both modes are the same computation (cascade P1, Fig. 7)."""
     w = W.small_variant(W.CONFIGS["c2_wan1p3b_seq"], heads=2, grid_h=9, grid_w=14, n_cached=3)

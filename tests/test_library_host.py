@@ -55,6 +55,10 @@ def test_config_validation():
     assert B.pool_bytes(_cfg(w, heads=0)) == 0
     assert B.pool_bytes(_cfg(w, rope_theta=0.0)) == 0
     assert B.pool_bytes(_cfg(w, max_inflight=0)) == 0
+    # limits: at most 8 blocks in flight and 32 slots in all
+    assert B.pool_bytes(_cfg(w, sink_blocks=1, window_blocks=23, max_inflight=8)) > 0
+    assert B.pool_bytes(_cfg(w, sink_blocks=1, window_blocks=24, max_inflight=8)) == 0
+    assert B.pool_bytes(_cfg(w, sink_blocks=0, window_blocks=6, max_inflight=9)) == 0
     with pytest.raises(B.CascadeAttnError) as e:
         B.Context(_cfg(w, head_dim=64, rope_dims=(24, 20, 20)))        # bf16 needs head_dim 128
     assert e.value.code == B.CA_EUNSUPPORTED
