@@ -61,6 +61,17 @@ class CascadeAttnError(RuntimeError):
 
 
 def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH) and "CASCADE_ATTN_LIB" not in os.environ:
+        # nothing built yet (a fresh checkout): build once, in-tree; there is no other path
+        import importlib.util
+        spec = importlib.util.spec_from_file_location(
+            "_cascade_attn_build", os.path.join(os.path.dirname(os.path.abspath(__file__)), "_build.py"))
+        builder = importlib.util.module_from_spec(spec)
+        try:
+            spec.loader.exec_module(builder)
+            builder.build()
+        except Exception as e:  # no hipcc, compile error, ...
+            raise ImportError(f"{LIB_PATH} is missing and could not be built: {e}") from e
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")

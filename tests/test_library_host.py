@@ -251,3 +251,15 @@ def test_lagged_scheduler_matches_closed_form():
         with pytest.raises(B.CascadeAttnError) as ex:
             B.Scheduler(5, 0, T, lag=bad)
         assert ex.value.code == B.CA_EINVAL
+
+
+def test_missing_library_is_an_import_error_not_a_fallback():
+    """There is no CPU path: with no library to load, importing the package fails."""
+    import subprocess
+    import sys
+    env = dict(os.environ, CASCADE_ATTN_LIB="/nonexistent/libcascade_attn.so")
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "try:\n    import paper_2511_20426_amd\nexcept ImportError as e:\n    print('ImportError', e); sys.exit(7)\n"
+            % ROOT)
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=120)
+    assert r.returncode == 7 and "is missing" in r.stdout, (r.returncode, r.stdout, r.stderr)
