@@ -51,8 +51,12 @@ struct AttnArgs {
   uint16_t* o;
   const uint8_t* pool;
   int32_t heads, pages_per_block, last_valid;
-  int32_t n_seg;                       // query segments: rows that share one visible prefix
-  int32_t seg_row0[kMaxSeg], seg_rows[kMaxSeg], seg_nvis[kMaxSeg], seg_tile0[kMaxSeg + 1];
+  // Query segments: rows that share one visible prefix.  All segments have the same number of
+  // row tiles, and the tiles of a head are numbered tile-major (tile t of every segment, then
+  // tile t+1 ...), so that any contiguous range of work items holds the same mix of long and
+  // short KV walks.
+  int32_t n_seg;
+  int32_t seg_row0[kMaxSeg], seg_rows[kMaxSeg], seg_nvis[kMaxSeg];
   int32_t kv_slot[kMaxKvBlocks];
   int32_t tiles_per_head, total_work, work_per_xcd;
   // Tail balancing: the last `split_items` work items of every XCD's range have their KV walk cut
@@ -77,9 +81,8 @@ __device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int work) {
   WorkItem w;
   w.h = work / a.tiles_per_head;
   const int tile = work - w.h * a.tiles_per_head;
-  int seg = 0;
-  while (seg + 1 < a.n_seg && tile >= a.seg_tile0[seg + 1]) ++seg;
-  w.row0 = a.seg_row0[seg] + (tile - a.seg_tile0[seg]) * kRowsPerWg;
+  const int t = tile / a.n_seg, seg = tile - t * a.n_seg;
+  w.row0 = a.seg_row0[seg] + t * kRowsPerWg;
   w.rows_end = a.seg_row0[seg] + a.seg_rows[seg];
   w.n_kvb = a.seg_nvis[seg];
   return w;
@@ -287,21 +290,17 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
     a.seg_row0[0] = 0;
     a.seg_rows[0] = p.n_q_blocks * p.block_tokens;
     a.seg_nvis[0] = p.n_vis[0];
-    a.seg_tile0[0] = 0;
     tiles = (a.seg_rows[0] + kRowsPerWg - 1) / kRowsPerWg;
-    a.seg_tile0[1] = tiles;
   } else {
-    // heaviest segment (latest block, longest prefix) first, so the tail of the launch is light
+    // one segment per query block, the longest prefix (latest block) first within a tile group
     a.n_seg = p.n_q_blocks;
     for (int j = 0; j < p.n_q_blocks; ++j) {
       const int i = p.n_q_blocks - 1 - j;
       a.seg_row0[j] = i * p.block_tokens;
       a.seg_rows[j] = p.block_tokens;
       a.seg_nvis[j] = p.n_vis[i];
-      a.seg_tile0[j] = tiles;
-      tiles += (p.block_tokens + kRowsPerWg - 1) / kRowsPerWg;
     }
-    a.seg_tile0[p.n_q_blocks] = tiles;
+    tiles = p.n_q_blocks * ((p.block_tokens + kRowsPerWg - 1) / kRowsPerWg);
   }
   a.tiles_per_head = tiles;
   a.total_work = tiles * p.heads;
