@@ -51,7 +51,7 @@ def cpu_baseline(w, seconds_target=15.0):
     g_q = w.n_cached
     states = [orc.CLEAN] * w.n_cached + [orc.NOISY] * w.n_inflight
     vis = orc.visibility(states, kv_g, [g_q], orc.BIDIRECTIONAL)
-    for _ in range(16):
+    for _ in range(64):                        # until seconds_target of oracle time
         q = W.store(rng.standard_normal((L, heads, D), dtype=np.float32) * 0.5, "bf16")
         k = W.store(rng.standard_normal((n_kv_blocks * L, heads, D), dtype=np.float32) * 0.5, "bf16")
         v = W.store(rng.standard_normal((n_kv_blocks * L, heads, D), dtype=np.float32) * 0.5, "bf16")
