@@ -239,6 +239,47 @@ def test_bf16_seeded_random_shapes(case):
     Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", f"random shape {case}")
 
 
+@pytest.mark.parametrize("case", range(24))
+def test_bf16_seeded_random_shapes_wide(case):
+    """Wider draws: up to 24 heads and 1620 tokens per block (launches with more work items than
+    CUs, i.e. split KV walks and the merge kernel), with or without a sink block, nominal or
+    peaked inputs, plus a random share of the same forward."""
+    rng = np.random.default_rng([4242, case])
+    fpb = int(rng.integers(1, 4))
+    gh, gw = int(rng.integers(2, 21)), int(rng.integers(2, 28))
+    nc, ni = int(rng.integers(0, 7)), int(rng.integers(1, 6))
+    heads = int(rng.choice([1, 2, 3, 5, 8, 12, 16, 24]))
+    mode = BI if rng.integers(0, 2) == 0 else CA
+    first = int(rng.integers(0, 9))
+    sink = int(rng.integers(0, 2))
+    base = W.CONFIGS["c5_wan1p3b_rollout" if sink else "c3_wan1p3b_cascade5"]
+    L = fpb * gh * gw
+    pairs = ni * L * (nc + ni) * L * heads
+    if pairs > 3e9:                           # keeps the oracle to a second or two per case
+        heads = max(1, int(heads * 3e9 / pairs))
+    w = W.small_variant(base, heads=heads, grid_h=gh, grid_w=gw, frames_per_block=fpb, n_cached=nc, n_inflight=ni)
+    if sink and nc > 0:
+        first = 0                             # the sink is block 0
+    scale = float(rng.choice([0.5, 0.5, 1.0, 2.0]))
+    _say(f"wide random shape {case}: heads={heads} frames={fpb} grid={gh}x{gw} L={L} cached={nc} inflight={ni} "
+         f"first={first} sink={sink} mode={mode} scale={scale}")
+    q, k, v = W.draw_config(w, seed=5000 + case, scale=scale)
+    cached = list(range(first, first + nc))
+    infl = list(range(first + nc, first + nc + ni))
+    pool = Hn.gpu_setup(w, k, v, cached, infl)
+    out = Hn.gpu_forward(w, pool, q, infl, mode)
+    ref = np.concatenate(Hn.oracle_forward(w, q, k, v, cached, infl, mode))
+    # logits grow with scale^2 and outputs with scale: the bars of the peaked variant, interpolated
+    grow = (scale / 0.5) ** 1.3
+    Hn.assert_close(out, ref, "bf16", f"wide random shape {case}", max_abs=2e-2 * grow, rel=5e-3 * grow)
+    if ni > 1:
+        f0 = int(rng.integers(0, ni))
+        cnt = int(rng.integers(1, ni - f0 + 1))
+        part = Hn.gpu_forward_share(w, pool, q, infl, mode, f0, cnt)
+        Hn.assert_close(part, ref[f0 * L:(f0 + cnt) * L], "bf16", f"wide random shape {case} share ({f0},{cnt})",
+                        max_abs=2e-2 * grow, rel=5e-3 * grow)
+
+
 @pytest.mark.parametrize("mode", [BI, CA])
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 def test_share_of_a_forward_every_block_range(mode, dtype):
