@@ -108,13 +108,25 @@ def test_rope3d_apply_matches_oracle(name):
     assert not wide[:, 0].any() and not wide[:, H + 1].any() and not wide[:, :, D:].any()
 
 
-@pytest.mark.parametrize("name", ["c1_tiny_f32", "c3_small"])
+_WRITE_GEOMETRIES = {
+    # heads, frames per block, rows, cols
+    "c3_small": (3, 3, 7, 11),
+    "one_column": (2, 1, 223, 1),     # a page spans 128 rows: too many angles for the kernel's trig table
+    "one_row": (1, 1, 1, 300),
+    "many_frames": (2, 5, 5, 7),      # a page spans several frames
+    "exact_pages": (1, 2, 8, 16),     # 256 tokens: no ragged page
+}
+
+
+@pytest.mark.parametrize("name", ["c1_tiny_f32"] + list(_WRITE_GEOMETRIES))
 def test_cache_write_pages_bit_exact_layout(name):
     """Pool bytes after kv_cache_append: V bit-exact, rotated K within one rounding, pad rows zero,
     each page at the page-pair index the oracle's rule gives."""
     import torch
-    if name == "c3_small":
-        w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=3, grid_h=7, grid_w=11, sink_blocks=1)
+    if name in _WRITE_GEOMETRIES:
+        heads, fpb, gh, gw = _WRITE_GEOMETRIES[name]
+        w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=heads, frames_per_block=fpb, grid_h=gh,
+                            grid_w=gw, sink_blocks=1)
     else:
         w = W.CONFIGS[name]
     from paper_2511_20426_amd.runner import CascadePool
