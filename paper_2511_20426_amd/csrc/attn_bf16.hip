@@ -51,14 +51,17 @@ struct AttnArgs {
   uint16_t* o;
   const uint8_t* pool;
   int32_t heads, pages_per_block, last_valid;
-  // Query segments: rows that share one visible prefix.  All segments have the same number of
-  // row tiles, and the tiles of a head are numbered tile-major (tile t of every segment, then
-  // tile t+1 ...), so that any contiguous range of work items holds the same mix of long and
-  // short KV walks.
-  int32_t n_seg;
+  // Query segments: rows that share one visible prefix (one segment in a bidirectional cascade,
+  // one per query block in a block-causal one, longest prefix first); all have tiles_per_seg row
+  // tiles.  A "column" is a (head, row tile) pair; XCD x owns columns [x*cols_per_xcd,
+  // (x+1)*cols_per_xcd) and works through them segment by segment: item i of an XCD is segment
+  // i / cols_per_xcd of column i % cols_per_xcd.  Workgroups that run together on an XCD then
+  // walk KV prefixes of one length, start and finish together, and stay in step on the same pages
+  // of the same few heads, which is what keeps those pages in the XCD's L2.
+  int32_t n_seg, tiles_per_seg, total_cols, cols_per_xcd;
   int32_t seg_row0[kMaxSeg], seg_rows[kMaxSeg], seg_nvis[kMaxSeg];
   int32_t kv_slot[kMaxKvBlocks];
-  int32_t tiles_per_head, total_work, work_per_xcd;
+  int32_t work_per_xcd;                // = cols_per_xcd * n_seg
   // Tail balancing: the last `split_items` work items of every XCD's range have their KV walk cut
   // into `split` page ranges, one workgroup each, so that the launch's last, partly filled round
   // of workgroups is shorter; their partial results meet in merge_partials_kernel.
@@ -74,14 +77,20 @@ constexpr int kPartialFloats = kRowsPerWg * kPartialRow;
 static_assert(size_t(kMaxPartials) * kPartialFloats * 4 == kAttnScratchBytes, "scratch size");
 
 struct WorkItem {
-  int h, row0, rows_end, n_kvb;
+  int h, row0, rows_end, n_kvb;     // h < 0: no such item (the last XCD may own fewer columns)
 };
 
-__device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int work) {
+__device__ __forceinline__ WorkItem decode_item(const AttnArgs& a, int xcd, int item) {
   WorkItem w;
-  w.h = work / a.tiles_per_head;
-  const int tile = work - w.h * a.tiles_per_head;
-  const int t = tile / a.n_seg, seg = tile - t * a.n_seg;
+  const int seg = item / a.cols_per_xcd;
+  const int col = xcd * a.cols_per_xcd + (item - seg * a.cols_per_xcd);
+  if (seg >= a.n_seg || col >= a.total_cols) {
+    w.h = -1;
+    w.row0 = w.rows_end = w.n_kvb = 0;
+    return w;
+  }
+  w.h = col / a.tiles_per_seg;
+  const int t = col - w.h * a.tiles_per_seg;
   w.row0 = a.seg_row0[seg] + t * kRowsPerWg;
   w.rows_end = a.seg_row0[seg] + a.seg_rows[seg];
   w.n_kvb = a.seg_nvis[seg];
@@ -108,7 +117,7 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l31 = lane & 31, hi = lane >> 5, sw = lane & 15;
 
-  // ---- which (head, row tile, page range): XCD x takes work items [x*work_per_xcd, (x+1)*work_per_xcd);
+  // ---- which (head, row tile, page range): XCD x takes its own work_per_xcd items;
   // inside an XCD the full items come first, then `split` workgroups per split item
   const int xcd = blockIdx.x & 7, nth = blockIdx.x >> 3;
   int item = nth, chunk = 0, n_chunks = 1;
@@ -117,9 +126,9 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
     chunk = (nth - a.full_items) % a.split;
     n_chunks = a.split;
   }
-  const int work = xcd * a.work_per_xcd + item;
-  if (item >= a.work_per_xcd || work >= a.total_work) return;
-  const WorkItem wi = decode_item(a, work);
+  if (item >= a.work_per_xcd) return;
+  const WorkItem wi = decode_item(a, xcd, item);
+  if (wi.h < 0) return;
   const int h = wi.h, row0 = wi.row0, rows_end = wi.rows_end, n_kvb = wi.n_kvb;
   const int all_pages = n_kvb * a.pages_per_block;
   const int page_lo = int(int64_t(all_pages) * chunk / n_chunks);
@@ -235,9 +244,8 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 // to the largest of their exponent references, summed and normalised.
 __global__ __launch_bounds__(256) void merge_partials_kernel(AttnArgs a) {
   const int xcd = blockIdx.x / a.split_items, sidx = blockIdx.x % a.split_items;
-  const int work = xcd * a.work_per_xcd + a.full_items + sidx;
-  if (work >= a.total_work) return;
-  const WorkItem wi = decode_item(a, work);
+  const WorkItem wi = decode_item(a, xcd, a.full_items + sidx);
+  if (wi.h < 0) return;
   const int r = threadIdx.x, row = wi.row0 + r;
   if (row >= wi.rows_end) return;
   const float* part = a.partials + size_t(xcd * a.split_items + sidx) * a.split * kPartialFloats + r * kPartialRow;
@@ -292,7 +300,7 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
     a.seg_nvis[0] = p.n_vis[0];
     tiles = (a.seg_rows[0] + kRowsPerWg - 1) / kRowsPerWg;
   } else {
-    // one segment per query block, the longest prefix (latest block) first within a tile group
+    // one segment per query block, the longest prefix (latest block) first
     a.n_seg = p.n_q_blocks;
     for (int j = 0; j < p.n_q_blocks; ++j) {
       const int i = p.n_q_blocks - 1 - j;
@@ -300,11 +308,12 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
       a.seg_rows[j] = p.block_tokens;
       a.seg_nvis[j] = p.n_vis[i];
     }
-    tiles = p.n_q_blocks * ((p.block_tokens + kRowsPerWg - 1) / kRowsPerWg);
+    tiles = (p.block_tokens + kRowsPerWg - 1) / kRowsPerWg;
   }
-  a.tiles_per_head = tiles;
-  a.total_work = tiles * p.heads;
-  a.work_per_xcd = (a.total_work + 7) / 8;
+  a.tiles_per_seg = tiles;
+  a.total_cols = tiles * p.heads;
+  a.cols_per_xcd = (a.total_cols + 7) / 8;
+  a.work_per_xcd = a.cols_per_xcd * a.n_seg;
   a.c = 1.4426950408889634f / sqrtf(float(p.head_dim));
   // Tail balancing.  One workgroup occupies a CU, an XCD has n_cu/8 of them, and all items of a
   // launch take about the same time: after floor(items / cus) full rounds, `rem` items would run
