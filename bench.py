@@ -222,8 +222,7 @@ def main() -> int:
         infl = list(range(b, b + C))
         if i_timed is not None:
             ev_a[i_timed][0].record()
-        for i, g in enumerate(infl):                                   # a1: publish K/V
-            pool.append(g, timesteps[i], 0, k_blocks[i], v_blocks[i])
+        pool.append_batch(infl, timesteps[:C], 0, k_blocks, v_blocks)   # a1: publish K/V, one launch
         if i_timed is not None:
             ev_a[i_timed][1].record()
         if args.share is None:
@@ -273,7 +272,7 @@ def main() -> int:
         "config": {"workload": w.name, "heads": H, "head_dim": D, "tokens_per_block": L,
                    "inflight_blocks": C, "cached_blocks": w.n_cached, "mode": args.mode,
                    "n_q": n_rot * L, "n_kv": (w.n_cached + C) * L, "flops_per_step": flops,
-                   "step": "%dx kv_cache_append + rope3d_apply(Q) + %s + promote/evict"
+                   "step": "kv_cache_append_batch(%d blocks) + rope3d_apply(Q) + %s + promote/evict"
                            % (C, "cascade_attn_forward" if args.share is None else "cascade_attn_forward_share")},
         "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,

@@ -112,6 +112,19 @@ int32_t kv_cache_append(ca_ctx* ctx, int64_t block_id, int32_t timestep, int32_t
                         int64_t tok_stride, int64_t head_stride,
                         void* hip_stream, int32_t* slot_out);
 
+/* The same for the n_blocks (1 .. 8) blocks in flight in one cascade iteration (Alg. 1: every
+ * block of the batch publishes its K/V before the shared attention), as one launch.  Entry i
+ * is block_ids[i] at timesteps[i] with K/V k_dev[i] / v_dev[i] (host arrays of device
+ * pointers; all tensors share tok_stride / head_stride).  The entries take effect in order and
+ * all or none: if any of them would fail as a single call, that code is returned and nothing
+ * has changed.  A block id may appear once (CA_EINVAL otherwise).  slots_out (optional) gets
+ * n_blocks slots. */
+int32_t kv_cache_append_batch(ca_ctx* ctx, int32_t n_blocks, const int64_t* block_ids,
+                              const int32_t* timesteps, int32_t prompt_epoch,
+                              const void* const* k_dev, const void* const* v_dev,
+                              int64_t tok_stride, int64_t head_stride, void* hip_stream,
+                              int32_t* slots_out);
+
 /* The block has run its cache step tc (Alg. 1: "block b completed tc"): NOISY -> CLEAN, or
  * -> SINK when block_id < sink_blocks (Sec. 3.3, first block kept as sink). */
 int32_t kv_cache_promote(ca_ctx* ctx, int64_t block_id);

@@ -24,7 +24,7 @@ CA_FREE, CA_NOISY, CA_CLEAN, CA_SINK = 0, 1, 2, 3
 
 # every symbol include/cascade_attn.h declares
 EXPORTS = (
-    "ca_pool_bytes", "ca_create", "ca_destroy", "kv_cache_append", "kv_cache_promote",
+    "ca_pool_bytes", "ca_create", "ca_destroy", "kv_cache_append", "kv_cache_append_batch", "kv_cache_promote",
     "kv_cache_evict", "kv_cache_retag", "kv_cache_snapshot", "kv_cache_page_index",
     "rope3d_apply", "rope3d_apply_strided", "cascade_attn_forward", "cascade_attn_forward_share", "ca_debug_visibility", "ca_set_kernel_variant",
     "ca_strerror", "ca_last_device_error",
@@ -91,6 +91,9 @@ def _load() -> C.CDLL:
     lib.kv_cache_append.argtypes = [vp, i64, i32, i32, vp, vp, i64, i64, vp, C.POINTER(i32)]
     lib.kv_cache_promote.restype = i32
     lib.kv_cache_promote.argtypes = [vp, i64]
+    lib.kv_cache_append_batch.restype = i32
+    lib.kv_cache_append_batch.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(i32), i32, C.POINTER(vp), C.POINTER(vp),
+                                          i64, i64, vp, C.POINTER(i32)]
     lib.kv_cache_evict.restype = i32
     lib.kv_cache_evict.argtypes = [vp, i64]
     lib.kv_cache_retag.restype = i32
@@ -200,6 +203,20 @@ class Context:
                                    C.c_void_p(v_ptr or None), tok_stride, head_stride,
                                    C.c_void_p(stream or None), C.byref(slot)), "kv_cache_append")
         return slot.value
+
+    def kv_cache_append_batch(self, block_ids: Sequence[int], timesteps: Sequence[int], prompt_epoch: int,
+                              k_ptrs: Sequence[int], v_ptrs: Sequence[int], tok_stride: int, head_stride: int,
+                              stream: int = 0) -> List[int]:
+        n = len(block_ids)
+        assert len(timesteps) == n and len(k_ptrs) == n and len(v_ptrs) == n
+        ids = (C.c_int64 * n)(*block_ids)
+        ts = (C.c_int32 * n)(*timesteps)
+        kp = (C.c_void_p * n)(*[p or None for p in k_ptrs])
+        vp = (C.c_void_p * n)(*[p or None for p in v_ptrs])
+        slots = (C.c_int32 * max(n, 1))()
+        _check(lib.kv_cache_append_batch(self._h, n, ids, ts, prompt_epoch, kp, vp, tok_stride, head_stride,
+                                         C.c_void_p(stream or None), slots), "kv_cache_append_batch")
+        return [int(slots[i]) for i in range(n)]
 
     def kv_cache_promote(self, block_id: int) -> None:
         _check(lib.kv_cache_promote(self._h, block_id), "kv_cache_promote")

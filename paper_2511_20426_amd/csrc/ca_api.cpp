@@ -67,24 +67,43 @@ int32_t ca_destroy(ca_ctx* ctx) {
 int32_t kv_cache_append(ca_ctx* ctx, int64_t block_id, int32_t timestep, int32_t prompt_epoch,
                         const void* k_dev, const void* v_dev, int64_t tok_stride,
                         int64_t head_stride, void* hip_stream, int32_t* slot_out) {
-  if (!ctx) return CA_EINVAL;
-  ca::CacheMeta& m = ctx->meta;
-  int32_t slot;
-  if (int32_t rc = m.check_append(block_id, &slot)) return rc;
+  return kv_cache_append_batch(ctx, 1, &block_id, &timestep, prompt_epoch, &k_dev, &v_dev, tok_stride,
+                               head_stride, hip_stream, slot_out);
+}
+
+int32_t kv_cache_append_batch(ca_ctx* ctx, int32_t n_blocks, const int64_t* block_ids,
+                              const int32_t* timesteps, int32_t prompt_epoch, const void* const* k_dev,
+                              const void* const* v_dev, int64_t tok_stride, int64_t head_stride,
+                              void* hip_stream, int32_t* slots_out) {
+  if (!ctx || !block_ids || !timesteps || n_blocks < 1 || n_blocks > ca::kMaxInflight) return CA_EINVAL;
+  // the entries are applied in order to a copy of the metadata: entry i sees what entries
+  // 0..i-1 did, and nothing has changed if any of them fails
+  ca::CacheMeta next = ctx->meta;
+  int32_t slots[ca::kMaxInflight];
+  int64_t first_frame[ca::kMaxInflight];
+  for (int i = 0; i < n_blocks; ++i) {
+    if (int32_t rc = next.check_append(block_ids[i], &slots[i])) return rc;
+    for (int j = 0; j < i; ++j)
+      if (block_ids[j] == block_ids[i]) return CA_EINVAL;      // one launch writes a slot once
+    next.commit_append(slots[i], block_ids[i], timesteps[i], prompt_epoch);
+    first_frame[i] = int64_t(next.cfg().frames_per_block) * block_ids[i];
+  }
   if (ctx->pool) {
     if (!k_dev || !v_dev) return CA_EINVAL;
-    if (!strides_ok(m.cfg(), k_dev, tok_stride, head_stride) ||
-        !strides_ok(m.cfg(), v_dev, tok_stride, head_stride))
-      return CA_EINVAL;
-    const ca_config& c = m.cfg();
-    const int32_t rc = ca::launch_cache_write(
-        rope_geom(m), c.dtype, k_dev, v_dev, tok_stride, head_stride,
-        int64_t(c.frames_per_block) * block_id, m.block_tokens(), c.page_tokens,
-        m.pages_per_block(), slot, ctx->pool, hip_stream);
+    const ca_config& c = next.cfg();
+    for (int i = 0; i < n_blocks; ++i) {
+      if (!k_dev[i] || !v_dev[i]) return CA_EINVAL;
+      if (!strides_ok(c, k_dev[i], tok_stride, head_stride) || !strides_ok(c, v_dev[i], tok_stride, head_stride))
+        return CA_EINVAL;
+    }
+    const int32_t rc = ca::launch_cache_write(rope_geom(next), c.dtype, n_blocks, k_dev, v_dev, tok_stride,
+                                              head_stride, first_frame, next.block_tokens(), c.page_tokens,
+                                              next.pages_per_block(), slots, ctx->pool, hip_stream);
     if (rc != CA_OK) return rc;
   }
-  m.commit_append(slot, block_id, timestep, prompt_epoch);
-  if (slot_out) *slot_out = slot;
+  ctx->meta = next;
+  if (slots_out)
+    for (int i = 0; i < n_blocks; ++i) slots_out[i] = slots[i];
   return CA_OK;
 }
 

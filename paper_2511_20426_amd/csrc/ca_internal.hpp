@@ -75,11 +75,12 @@ int32_t launch_rope_apply(const RopeGeom& g, int dtype, const void* x, void* y, 
                           int64_t first_frame, int64_t tok_stride, int64_t head_stride,
                           int64_t y_tok_stride, int64_t y_head_stride, void* stream);
 
-// Fused K-rotation + K/V page store of one block into its slot.
-int32_t launch_cache_write(const RopeGeom& g, int dtype, const void* k, const void* v,
-                           int64_t tok_stride, int64_t head_stride, int64_t first_frame,
-                           int32_t block_tokens, int32_t page_tokens, int32_t pages_per_block,
-                           int32_t slot, void* pool, void* stream);
+// Fused K-rotation + K/V page store of n_blocks (1..kMaxInflight) blocks into their slots, one
+// launch for all of them (bf16).
+int32_t launch_cache_write(const RopeGeom& g, int dtype, int32_t n_blocks, const void* const* k,
+                           const void* const* v, int64_t tok_stride, int64_t head_stride,
+                           const int64_t* first_frame, int32_t block_tokens, int32_t page_tokens,
+                           int32_t pages_per_block, const int32_t* slot, void* pool, void* stream);
 
 struct AttnPlan {
   int32_t heads, head_dim, page_tokens, pages_per_block, block_tokens;

@@ -172,16 +172,39 @@ struct TrigTable {
   int32_t n_f, n_y, n_x;       // axis values tabulated: consecutive frames / rows (mod grid_h) / columns (mod grid_w)
 };
 
-struct PagedArgs {
+struct PagedBlock {            // one block of a launch (grid.z picks it)
+  const uint16_t* k;
+  const uint16_t* v;
+  int64_t first_frame;
+  int32_t slot;
+};
+
+struct PagedBatch {
+  PagedBlock b[kMaxInflight];
+  uint8_t* pool;
+  int64_t tok_stride, head_stride;
+  int32_t block_tokens, pages_per_block, heads_per_group;
+  TrigTable tab;               // n_f == 0: no table (geometry too large for LDS), evaluate per thread
+};
+
+struct PagedArgs {             // what the kernel body works with: the batch's entry for this workgroup
   const uint16_t* k;
   const uint16_t* v;
   uint8_t* pool;
   int64_t tok_stride, head_stride, first_frame;
   int32_t block_tokens, pages_per_block, slot, heads_per_group;
-  TrigTable tab;               // n_f == 0: no table (geometry too large for LDS), evaluate per thread
+  TrigTable tab;
 };
 
-__global__ __launch_bounds__(256) void cache_write_bf16_kernel(RopeGeom g, PagedArgs a) {
+__global__ __launch_bounds__(256) void cache_write_bf16_kernel(RopeGeom g, PagedBatch batch) {
+  PagedArgs a;
+  {
+    const PagedBlock& blk = batch.b[blockIdx.z];
+    a.k = blk.k; a.v = blk.v; a.first_frame = blk.first_frame; a.slot = blk.slot;
+    a.pool = batch.pool; a.tok_stride = batch.tok_stride; a.head_stride = batch.head_stride;
+    a.block_tokens = batch.block_tokens; a.pages_per_block = batch.pages_per_block;
+    a.heads_per_group = batch.heads_per_group; a.tab = batch.tab;
+  }
   __shared__ uint32_t vt[kPage * kVRowWords];
   extern __shared__ float2 trig[];   // [n_f][pairs_t] then [n_y][pairs_h] then [n_x][pairs_w]
   const int t = threadIdx.x;
@@ -360,25 +383,30 @@ int32_t launch_rope_apply(const RopeGeom& g, int dtype, const void* x, void* y, 
   return finish_launch("rope_cache.hip");
 }
 
-int32_t launch_cache_write(const RopeGeom& g, int dtype, const void* k, const void* v,
-                           int64_t tok_stride, int64_t head_stride, int64_t first_frame,
-                           int32_t block_tokens, int32_t page_tokens, int32_t pages_per_block,
-                           int32_t slot, void* pool, void* stream) {
+int32_t launch_cache_write(const RopeGeom& g, int dtype, int32_t n_blocks, const void* const* k,
+                           const void* const* v, int64_t tok_stride, int64_t head_stride,
+                           const int64_t* first_frame, int32_t block_tokens, int32_t page_tokens,
+                           int32_t pages_per_block, const int32_t* slot, void* pool, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
+  if (n_blocks < 1 || n_blocks > kMaxInflight) return CA_EINVAL;
   if (dtype == CA_BF16) {
     if (g.head_dim != 128 || page_tokens != kPage) return CA_EUNSUPPORTED;
-    PagedArgs a{};
-    a.k = static_cast<const uint16_t*>(k);
-    a.v = static_cast<const uint16_t*>(v);
+    PagedBatch a{};
+    for (int i = 0; i < n_blocks; ++i) {
+      a.b[i].k = static_cast<const uint16_t*>(k[i]);
+      a.b[i].v = static_cast<const uint16_t*>(v[i]);
+      a.b[i].first_frame = first_frame[i];
+      a.b[i].slot = slot[i];
+    }
     a.pool = static_cast<uint8_t*>(pool);
-    a.tok_stride = tok_stride; a.head_stride = head_stride; a.first_frame = first_frame;
-    a.block_tokens = block_tokens; a.pages_per_block = pages_per_block; a.slot = slot;
+    a.tok_stride = tok_stride; a.head_stride = head_stride;
+    a.block_tokens = block_tokens; a.pages_per_block = pages_per_block;
     int groups = 1;
-    while (pages_per_block * groups < 1024 && groups < g.heads) groups *= 2;
+    while (pages_per_block * n_blocks * groups < 1024 && groups < g.heads) groups *= 2;
     groups = groups > g.heads ? g.heads : groups;
     a.heads_per_group = (g.heads + groups - 1) / groups;
     const dim3 grid((unsigned)pages_per_block,
-                    (unsigned)((g.heads + a.heads_per_group - 1) / a.heads_per_group));
+                    (unsigned)((g.heads + a.heads_per_group - 1) / a.heads_per_group), (unsigned)n_blocks);
     // axis values a 128-token page can touch: consecutive tokens, so consecutive columns (all of
     // them once the page is longer than a row), rows and frames
     const int plane = g.grid_h * g.grid_w;
@@ -395,15 +423,17 @@ int32_t launch_cache_write(const RopeGeom& g, int dtype, const void* k, const vo
     a.tab = tab;
     hipLaunchKernelGGL(cache_write_bf16_kernel, grid, dim3(256), tab_bytes, s, g, a);
   } else {
-    GenericArgs a{};
-    a.x = k; a.v = v; a.y = pool;
-    a.n_tokens = int64_t(pages_per_block) * page_tokens; a.first_frame = first_frame;
-    a.valid_tokens = block_tokens;
-    a.tok_stride = tok_stride; a.head_stride = head_stride;
-    a.page_tokens = page_tokens; a.pages_per_block = pages_per_block; a.slot = slot;
-    a.heads_per_group = g.heads;
-    const dim3 grid((unsigned)((a.n_tokens + 3) / 4), 1);
-    hipLaunchKernelGGL((rope_generic_kernel<float, 1>), grid, dim3(256), 0, s, g, a);
+    for (int i = 0; i < n_blocks; ++i) {           // the fp32 path is for tiny cases: one launch per block
+      GenericArgs a{};
+      a.x = k[i]; a.v = v[i]; a.y = pool;
+      a.n_tokens = int64_t(pages_per_block) * page_tokens; a.first_frame = first_frame[i];
+      a.valid_tokens = block_tokens;
+      a.tok_stride = tok_stride; a.head_stride = head_stride;
+      a.page_tokens = page_tokens; a.pages_per_block = pages_per_block; a.slot = slot[i];
+      a.heads_per_group = g.heads;
+      const dim3 grid((unsigned)((a.n_tokens + 3) / 4), 1);
+      hipLaunchKernelGGL((rope_generic_kernel<float, 1>), grid, dim3(256), 0, s, g, a);
+    }
   }
   return finish_launch("rope_cache.hip");
 }

@@ -90,8 +90,13 @@ class CascadeRollout:
         if self.batch_qkv_fn is not None:
             staged = self.batch_qkv_fn(batch)
         n = len(batch)
+        ks, vs = [s[1] for s in staged], [s[2] for s in staged]
+        if all(t.stride() == ks[0].stride() for t in ks + vs):
+            pool.append_batch([g for g, _, _ in batch], [t for _, _, t in batch], self.epoch, ks, vs)
+        else:                                  # one launch needs one set of strides
+            for (g, ti, t), k, v in zip(batch, ks, vs):
+                pool.append(g, t, self.epoch, k, v)
         for i, ((g, ti, t), (q, k, v)) in enumerate(zip(batch, staged)):
-            pool.append(g, t, self.epoch, k, v)
             # each block's queries are rotated from wherever they live into the packed tensor
             pool.rope(q, pool.frames_per_block * g, out=self._qr[i * L:(i + 1) * L])
         infl = [g for g, _, _ in batch]

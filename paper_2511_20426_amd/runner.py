@@ -58,6 +58,17 @@ class CascadePool:
         return self.ctx.kv_cache_append(block_id, timestep, epoch, k.data_ptr(), v.data_ptr(),
                                         k.stride(0), k.stride(1), self._stream())
 
+    def append_batch(self, block_ids: Sequence[int], timesteps: Sequence[int], epoch: int,
+                     ks: Sequence[torch.Tensor], vs: Sequence[torch.Tensor]) -> list[int]:
+        """All blocks of one cascade iteration in one launch; the tensors share their strides."""
+        for k, v in zip(ks, vs):
+            self._check(k); self._check(v)
+            assert k.shape[0] == self.block_tokens and k.shape == v.shape
+            assert k.stride() == ks[0].stride() and v.stride() == ks[0].stride()
+        return self.ctx.kv_cache_append_batch(list(block_ids), list(timesteps), epoch,
+                                              [k.data_ptr() for k in ks], [v.data_ptr() for v in vs],
+                                              ks[0].stride(0), ks[0].stride(1), self._stream())
+
     def rope(self, x: torch.Tensor, first_frame: int, out: torch.Tensor | None = None) -> torch.Tensor:
         """Rotate x [n, H, D] (any token / head strides) into `out` (its own strides; default: a new
         contiguous tensor).  x is out is allowed."""
@@ -109,8 +120,8 @@ def attention_layer(pool: CascadePool, x: torch.Tensor, w_qkv: torch.Tensor, w_o
     n = len(inflight) * L
     assert x.shape == (n, H * D) and w_qkv.shape == (3 * H * D, H * D) and w_out.shape == (H * D, H * D)
     qkv = linear(x, w_qkv).view(n, 3, H, D)
-    for i, (g, t) in enumerate(zip(inflight, timesteps)):
-        pool.append(g, t, epoch, qkv[i * L:(i + 1) * L, 1], qkv[i * L:(i + 1) * L, 2])
+    blocks = [qkv[i * L:(i + 1) * L] for i in range(len(inflight))]
+    pool.append_batch(inflight, timesteps, epoch, [b[:, 1] for b in blocks], [b[:, 2] for b in blocks])
     q_rot = pool.rope(qkv[:, 0], pool.frames_per_block * inflight[0])     # strided view -> contiguous
     o = pool.forward(q_rot, inflight, mode)
     return linear(o.view(n, H * D), w_out)

@@ -165,6 +165,34 @@ def test_cache_write_pages_bit_exact_layout(name):
                     assert not Kp[nv:].any() and not Vp[nv:].any()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_append_batch_writes_the_same_pool_bytes(dtype):
+    """One launch for the blocks of an iteration against one kv_cache_append per block: the
+    pools must be identical byte for byte (strided K/V views out of a packed tensor)."""
+    import torch
+    from paper_2511_20426_amd.runner import CascadePool
+    if dtype == "bf16":
+        w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=5, grid_h=9, grid_w=13, sink_blocks=1)
+    else:
+        w = W.small_variant(W.CONFIGS["c1_tiny_f32"], heads=3, grid_h=5, grid_w=7, max_inflight=4, n_inflight=4)
+    L, H, D = w.block_tokens, w.heads, w.head_dim
+    one, many = CascadePool.for_workload(w), CascadePool.for_workload(w)
+    rng = np.random.default_rng(17)
+    ids = [2, 3, 4, 5]
+    packed = [Hn.to_torch(W.store(rng.standard_normal((L, 3, H, D), dtype=np.float32), w.dtype), w.dtype)
+              for _ in ids]
+    # the scratch area behind the pages is not part of the comparison: clear both pools first
+    one.pool.zero_(); many.pool.zero_()
+    for g, x in zip(ids, packed):
+        one.append(g, 250 * g, 1, x[:, 1], x[:, 2])
+    slots = many.append_batch(ids, [250 * g for g in ids], 1, [x[:, 1] for x in packed], [x[:, 2] for x in packed])
+    torch.cuda.synchronize()
+    assert [s.astuple() for s in one.ctx.kv_cache_snapshot()] == [s.astuple() for s in many.ctx.kv_cache_snapshot()]
+    assert slots == [s.slot for s in many.ctx.kv_cache_snapshot()]
+    assert torch.equal(one.pool, many.pool)
+    assert bool(one.pool.any())
+
+
 # --------------------------------------------------------------------------- bf16 MFMA path, small shapes
 
 SMALL = [

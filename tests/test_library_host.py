@@ -263,3 +263,41 @@ def test_missing_library_is_an_import_error_not_a_fallback():
             % ROOT)
     r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=120)
     assert r.returncode == 7 and "is missing" in r.stdout, (r.returncode, r.stdout, r.stderr)
+
+
+def test_append_batch_is_the_sequence_of_appends_or_nothing():
+    """kv_cache_append_batch on a metadata-only context: same slots and tags as one call per
+    entry in order; any failing entry leaves everything as it was."""
+    w = W.CONFIGS["c5_wan1p3b_rollout"]
+    a, b = B.Context(_cfg(w)), B.Context(_cfg(w))
+    cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, w.max_inflight, w.pages_per_block, w.heads)
+    for step in range(30):
+        blk, batch, slots = orc.rollout_step(cache, step, W.TIMESTEPS, epoch=step // 7)
+        ids, ts = [g for g, _ in batch], [t for _, t in batch]
+        got = a.kv_cache_append_batch(ids, ts, step // 7, [0] * len(ids), [0] * len(ids), 0, 0)
+        assert got == slots
+        for g, t in batch:
+            b.kv_cache_append(g, t, step // 7, 0, 0, 0, 0)
+        assert _snap(a) == _snap(b) == cache.snapshot()
+        evicted = orc.rollout_finish(cache, blk, batch)
+        if batch[0][1] == 0:
+            for c in (a, b):
+                c.kv_cache_promote(blk)
+                if evicted is not None:
+                    c.kv_cache_evict(evicted)
+    before = _snap(a)
+    live = [s[1] for s in before if s[2] == B.CA_NOISY]
+    ring = w.window_blocks + w.max_inflight
+
+    def fails(code, ids, ts=None):
+        with pytest.raises(B.CascadeAttnError) as e:
+            a.kv_cache_append_batch(ids, ts or [0] * len(ids), 9, [0] * len(ids), [0] * len(ids), 0, 0)
+        assert e.value.code == code, (e.value.code, code)
+        assert _snap(a) == before
+
+    fails(B.CA_EINVAL, [])
+    fails(B.CA_EINVAL, [live[0], live[0]])                       # a block twice in one launch
+    fails(B.CA_EINVAL, list(range(live[0], live[0] + 9)))        # more than 8 entries
+    fails(B.CA_ENOSPC, [live[0], live[0] + ring])                # second entry's slot is the first's
+    fails(B.CA_ESTATE, [live[-1], 0])                            # the sink block is finished
+    fails(B.CA_EINVAL, [live[0], -3])
