@@ -169,6 +169,15 @@ def test_error_paths_leave_state_unchanged():
     fails(B.CA_ESTATE, ctx.kv_cache_promote, 0)
     fails(B.CA_ESTATE, ctx.kv_cache_append, 0, 0, 0, 0, 0, 0, 0)
     fails(B.CA_ESTATE, ctx.debug_visibility, [0], B.CA_BIDIRECTIONAL)   # a finished block is not in flight
+    ctx.kv_cache_promote(1)                                  # block 1 is past the sink: CLEAN
+    before = _snap(ctx)
+    assert before[1][2] == B.CA_CLEAN
+    fails(B.CA_ESTATE, ctx.kv_cache_append, 1, 0, 0, 0, 0, 0, 0)       # a clean block is not rewritten
+    fails(B.CA_ESTATE, ctx.kv_cache_promote, 1)
+    fails(B.CA_ESTATE, ctx.debug_visibility, [1], B.CA_BLOCK_CAUSAL)
+    ctx.kv_cache_append(2, 500, 0, 0, 0, 0, 0)
+    before = _snap(ctx)
+    fails(B.CA_EINVAL, ctx.debug_visibility, [2, 2], B.CA_BIDIRECTIONAL)   # the same block twice
     # retag on an empty cache is a no-op that succeeds
     empty = B.Context(_cfg(w))
     empty.kv_cache_retag(3)
