@@ -4,8 +4,8 @@
  * One forward of a block-cascaded video DiT layer: the queries of several in-flight
  * latent-frame blocks, each at its own denoising step, attend to a shared KV pool that
  * holds the clean cache of finished blocks (rolling window, optional sink) and the K/V
- * of the in-flight blocks themselves (paper Sec. 3.2 "mini-batches ... with shared
- * attention", Sec. 3.3 "shared KV pool", Alg. 1).
+ * of the in-flight blocks themselves (paper Sec. 3.2: the blocks of an iteration are batched
+ * and attend together; Sec. 3.3: one KV pool that every block reads; Alg. 1).
  *
  * Conventions
  *   - Every function returns int32_t: CA_OK (0) or a negative CA_E* code.  Nothing throws,
@@ -70,7 +70,7 @@ enum {
 };
 
 enum { CA_F32 = 0, CA_BF16 = 1 };
-enum { CA_BIDIRECTIONAL = 0, CA_BLOCK_CAUSAL = 1 };          /* Sec. 3.4 / Sec. 4.2 "causal P4" */
+enum { CA_BIDIRECTIONAL = 0, CA_BLOCK_CAUSAL = 1 };          /* Sec. 3.4 / Sec. 4.2 (the causal P4 variant) */
 enum { CA_FREE = 0, CA_NOISY = 1, CA_CLEAN = 2, CA_SINK = 3 };
 
 typedef struct ca_ctx ca_ctx;
@@ -125,7 +125,7 @@ int32_t kv_cache_append_batch(ca_ctx* ctx, int32_t n_blocks, const int64_t* bloc
                               int64_t tok_stride, int64_t head_stride, void* hip_stream,
                               int32_t* slots_out);
 
-/* The block has run its cache step tc (Alg. 1: "block b completed tc"): NOISY -> CLEAN, or
+/* The block has run its cache step tc (Alg. 1: the step at which b advances): NOISY -> CLEAN, or
  * -> SINK when block_id < sink_blocks (Sec. 3.3, first block kept as sink). */
 int32_t kv_cache_promote(ca_ctx* ctx, int64_t block_id);
 
