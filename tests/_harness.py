@@ -96,7 +96,8 @@ def gpu_forward(w: W.Workload, pool, q, inflight_g, mode):
     assert list(inflight_g) == list(range(inflight_g[0], inflight_g[0] + len(inflight_g)))
     qt = to_torch(q, w.dtype)
     qr = pool.rope(qt, w.frames_per_block * inflight_g[0])
-    out = pool.forward(qr, inflight_g, mode)
+    # the result buffer starts as NaN: a row the launch failed to write cannot pass for a result
+    out = pool.forward(qr, inflight_g, mode, out=torch.full_like(qr, float("nan")))
     torch.cuda.synchronize()
     return from_torch(out, w.dtype)
 
@@ -108,7 +109,7 @@ def gpu_forward_share(w: W.Workload, pool, q, inflight_g, mode, first, count):
     L = w.block_tokens
     qt = to_torch(np.ascontiguousarray(q[first * L:(first + count) * L]), w.dtype)
     qr = pool.rope(qt, w.frames_per_block * inflight_g[first])
-    out = pool.forward(qr, inflight_g, mode, share=(first, count))
+    out = pool.forward(qr, inflight_g, mode, out=torch.full_like(qr, float("nan")), share=(first, count))
     torch.cuda.synchronize()
     return from_torch(out, w.dtype)
 
