@@ -748,9 +748,11 @@ def test_layer_linear_qkv_and_output_projection_shapes_sampled():
     for N in (15360, 5120):
         x, w = W.draw_linear(M, N, K, seed=43)
         _say(f"linear M={M} N={N} K={K} sampled rows={len(rows)}")
-        y = linear(Hn.to_torch(x, "bf16"), Hn.to_torch(w, "bf16"))
+        y = linear(Hn.to_torch(x, "bf16"), Hn.to_torch(w, "bf16"),
+                   out=torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0"))
         torch.cuda.synchronize()
         got = Hn.from_torch(y, "bf16")
+        assert np.isfinite(got).all()                        # every tile of the result was written
         _linear_check(got, x, w, rows, f"linear {M}x{N}x{K}")
 
 
