@@ -33,6 +33,7 @@ class IterationRecord:
     completed: int                             # block that ran tc and became clean, or -1
     evicted: int                               # block dropped from the window, or -1
     ms: Optional[float] = None                 # device time of the iteration (events), if timed
+    events: Optional[tuple] = field(default=None, repr=False, compare=False)   # (start, end) until run() reads them
 
 
 @dataclass
@@ -119,7 +120,7 @@ class CascadeRollout:
                 self.out_fn(g, ti, o[i * L:(i + 1) * L])
         rec = IterationRecord(it, batch, emitted, completed, evicted)
         if self.timed:
-            rec._events = (e0, e1)
+            rec.events = (e0, e1)
         self.records.append(rec)
         return rec
 
@@ -129,8 +130,9 @@ class CascadeRollout:
         if self.timed:
             torch.cuda.synchronize(self.pool.device)
             for r in self.records:
-                e0, e1 = r._events
-                r.ms = e0.elapsed_time(e1)
+                if r.events is not None:
+                    r.ms = r.events[0].elapsed_time(r.events[1])
+                    r.events = None
         return self.records
 
 
