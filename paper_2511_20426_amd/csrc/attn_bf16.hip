@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(AttnArgs a) {
 int32_t attn_bf16_variant_ok(int variant) { return variant == 0 || variant == 1 ? CA_OK : CA_EINVAL; }
 
 int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
-                         void* scratch, void* stream) {
+                         void* scratch, int max_partials, void* stream) {
   if (p.head_dim != 128 || p.page_tokens != 128) return CA_EUNSUPPORTED;
   if (attn_bf16_variant_ok(variant) != CA_OK) return CA_EINVAL;
   AttnArgs a{};
@@ -330,7 +330,7 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
   if (scratch && variant == 0 && rem > 0 && a.work_per_xcd > cus_per_xcd) {
     int split = cus_per_xcd / rem;
     if (split > 8) split = 8;
-    while (split > 1 && (min_pages < 8 * split || 8 * rem * split > kMaxPartials)) --split;
+    while (split > 1 && (min_pages < 8 * split || 8 * rem * split > max_partials)) --split;
     if (split > 1) {
       a.split = split;
       a.split_items = rem;

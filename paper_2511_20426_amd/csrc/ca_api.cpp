@@ -193,7 +193,8 @@ int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev, const int64_t
   }
   if (c.dtype == CA_BF16)
     return ca::launch_attn_bf16(p, ctx->variant, q_dev, out_dev, ctx->pool,
-                                static_cast<uint8_t*>(ctx->pool) + m.page_bytes_total(), hip_stream);
+                                static_cast<uint8_t*>(ctx->pool) + m.page_bytes_total(), ca::kMaxPartials,
+                                hip_stream);
   return ca::launch_attn_f32(p, q_dev, out_dev, ctx->pool, hip_stream);
 }
 

@@ -92,8 +92,10 @@ struct AttnPlan {
 };
 
 int32_t launch_attn_f32(const AttnPlan& p, const void* q, void* out, const void* pool, void* stream);
+// scratch: room for max_partials partial results (kAttnScratchBytes / kMaxPartials bytes each) of
+// split work items, or nullptr / 0: then no KV walk is split.
 int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
-                         void* scratch, void* stream);
+                         void* scratch, int max_partials, void* stream);
 int32_t attn_bf16_variant_ok(int variant);
 
 // Launchers end with this: CA_OK, or CA_EDEVICE after recording the HIP error text.
