@@ -1,5 +1,5 @@
-// Host-side cascade scheduler: the control flow of Algorithm 1 ("Multi-GPU Inference with Block
-// Cascading"), integers only, generalised by the lag between consecutive blocks.
+// Host-side cascade scheduler: the control flow of Algorithm 1 (the multi-GPU cascade schedule),
+// integers only, generalised by the lag between consecutive blocks.
 //
 // Every block walks the timestep list T one entry per iteration; block j enters `lag` iterations
 // after block j-1.  In iteration n the batch therefore holds the blocks j with
