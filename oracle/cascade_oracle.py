@@ -8,13 +8,13 @@ invariants; nothing here is "parity unpinned".
 
 What is computed (paper passages):
 
-* blocks of `Fb` latent frames; a block is bidirectional inside (Sec. 3.1,
-  "Block-causal video generation");
+* blocks of `Fb` latent frames; a block is bidirectional inside (Sec. 3.1, the
+  paragraph on block-causal generation);
 * several in-flight blocks at different denoising steps are batched into one
   forward and share attention (Sec. 3.2 last paragraph); their K/V live in one
   shared KV pool next to the clean cache of finished blocks (Sec. 3.3);
 * across the cascade attention is bidirectional (Sec. 3.4) or block-causal
-  ("causal P4", Sec. 4.2; Sec. 3.2: block i attends to blocks i-k and itself);
+  (the causal P4 variant, Sec. 4.2; Sec. 3.2: block i attends to blocks i-k and itself);
 * a rolling window of clean blocks with eviction of the oldest, optionally a
   sink block kept for ever (Sec. 2.3, Sec. 3.3);
 * the per-iteration schedule of Algorithm 1 (block b+i runs at T[tau-i]);
