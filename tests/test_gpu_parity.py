@@ -622,20 +622,23 @@ def test_c5_rollout_ring_buffer():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("mode,lag", [(BI, None), (CA, None), (BI, 2), (CA, 3), (BI, 5)])
-def test_algorithm1_rollout_driver(mode, lag):
+@pytest.mark.parametrize("mode,lag,sink,window", [(BI, None, 1, 2), (CA, None, 1, 2), (BI, 2, 1, 2), (CA, 3, 1, 2),
+                                                  (BI, 5, 1, 2), (CA, None, 2, 0), (BI, None, 0, 1)])
+def test_algorithm1_rollout_driver(mode, lag, sink, window):
     """A full 13-block rollout driven by the library's scheduler (ramp-up, steady state, drain) on
-    a small token grid, 1 sink block + 2-block window: every output row of every iteration
+    a small token grid, 1 sink block + 2-block window (also: two sinks and no window at all; no
+    sink and a one-block window): every output row of every iteration
     against the oracle, which follows its own transcription of Alg. 1 (lag None) or its closed
     form of the lagged cascades (lag 2, 3, 5: three, two, one block in flight) and its own cache
     state machine."""
     import torch
     from paper_2511_20426_amd.runner import CascadePool
     from paper_2511_20426_amd.rollout import CascadeRollout
-    w = W.small_variant(W.CONFIGS["c5_wan1p3b_rollout"], heads=2, grid_h=6, grid_w=9, window_blocks=2)
+    w = W.small_variant(W.CONFIGS["c5_wan1p3b_rollout"], heads=2, grid_h=6, grid_w=9, sink_blocks=sink,
+                        window_blocks=window)
     L, H = w.block_tokens, w.heads
     n_blocks = 13
-    _say(f"alg1 rollout driver: L={L} heads={H} mode={mode} lag={lag}")
+    _say(f"alg1 rollout driver: L={L} heads={H} mode={mode} lag={lag} sink={sink} window={window}")
     pool = CascadePool.for_workload(w)
     host, outs = {}, {}
 

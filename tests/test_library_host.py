@@ -127,6 +127,35 @@ def test_rollout_metadata_matches_oracle_bit_exact():
     assert max(s[1] for s in snap) >= 3 * (w.window_blocks + w.max_inflight)
 
 
+@pytest.mark.parametrize("sink,window", [(0, 6), (2, 3), (1, 1), (3, 0), (0, 27)])
+def test_rollout_metadata_other_cache_shapes(sink, window):
+    """The same walk for other cache shapes: no sink, several sink blocks, a one-block window, no
+    window at all (only sinks and the blocks in flight), the largest window a context takes."""
+    w = W.CONFIGS["c5_wan1p3b_rollout"]
+    ctx = B.Context(_cfg(w, sink_blocks=sink, window_blocks=window))
+    cache = orc.KVCacheOracle(sink, window, w.max_inflight, w.pages_per_block, w.heads)
+    for step in range(3 * (window + w.max_inflight) + 9):
+        b, batch = orc.cascade_schedule(step, W.TIMESTEPS, w.max_inflight)
+        ids, ts = [g for g, _ in batch], [t for _, t in batch]
+        assert ctx.kv_cache_append_batch(ids, ts, 0, [0] * len(ids), [0] * len(ids), 0, 0) == \
+            [cache.append(g, t, 0) for g, t in batch]
+        order, states, slots = cache.kv_order(ids)
+        for mode in (B.CA_BIDIRECTIONAL, B.CA_BLOCK_CAUSAL):
+            vis, kv_ids = ctx.debug_visibility(ids, mode)
+            assert kv_ids == order
+            np.testing.assert_array_equal(np.array(vis, dtype=np.uint8), orc.visibility(states, order, ids, mode))
+        if batch[0][1] == 0:
+            ctx.kv_cache_promote(b)
+            cache.promote(b)
+            win = cache.clean_window()
+            if len(win) > window:
+                ctx.kv_cache_evict(win[0])
+                cache.evict(win[0])
+        assert _snap(ctx) == cache.snapshot()
+    states = [s[2] for s in _snap(ctx)]
+    assert states.count(B.CA_SINK) == sink and states.count(B.CA_CLEAN) == window
+
+
 def test_error_paths_leave_state_unchanged():
     w = W.CONFIGS["c5_wan1p3b_rollout"]
     ctx = B.Context(_cfg(w, window_blocks=2, max_inflight=2))
