@@ -114,8 +114,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
 
 int32_t launch_gemm_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                          int64_t ldx, int64_t ldw, int64_t ldy, void* stream) {
-  if (M < 1 || M > (int64_t(1) << 30) || N < kTile || N % kTile != 0 || K < 128 || K % 128 != 0) return CA_EUNSUPPORTED;
+  if (M < 0) return CA_EINVAL;
+  if (M > (int64_t(1) << 30) || N < kTile || N % kTile != 0 || K < 128 || K % 128 != 0) return CA_EUNSUPPORTED;
   if (ldx < K || ldw < K || ldy < N || ldx % 8 != 0 || ldw % 8 != 0 || ldy % 8 != 0) return CA_EINVAL;
+  if (M == 0) return CA_OK;                       // nothing to do
   if (ldx * 2 * kTile >= (int64_t(1) << 31) || ldw * 2 * kTile >= (int64_t(1) << 31)) return CA_EUNSUPPORTED;
   GemmArgs a{};
   a.x = static_cast<const uint16_t*>(x);

@@ -768,10 +768,28 @@ def test_layer_linear_rejects_unsupported_shapes():
                        ((p, p, p, 256, 256, 96, 512, 512, 512), B.CA_EUNSUPPORTED),    # k_in not a multiple of 128
                        ((p, p, p, 256, 256, 128, 64, 512, 512), B.CA_EINVAL),          # row stride shorter than the row
                        ((p, p, p + 2, 256, 256, 128, 512, 512, 512), B.CA_EINVAL),     # misaligned
-                       ((0, p, p, 256, 256, 128, 512, 512, 512), B.CA_EINVAL)):
+                       ((0, p, p, 256, 256, 128, 512, 512, 512), B.CA_EINVAL),
+                       ((p, p, p, -1, 256, 128, 512, 512, 512), B.CA_EINVAL)):
         with pytest.raises(B.CascadeAttnError) as e:
             B.layer_linear_bf16(*args)
         assert e.value.code == code, args
+    # empty inputs are no-ops that succeed and write nothing
+    t.fill_(3.0)
+    B.layer_linear_bf16(p, p, p, 0, 256, 128, 512, 512, 512)
+    torch.cuda.synchronize()
+    assert bool((t == 3.0).all())
+
+
+def test_empty_rotation_is_a_no_op():
+    import torch
+    from paper_2511_20426_amd.runner import CascadePool
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=4, grid_w=5)
+    pool = CascadePool.for_workload(w)
+    x = torch.full((4, w.heads, w.head_dim), 2.0, dtype=torch.bfloat16, device="cuda:0")
+    pool.ctx.rope3d_apply(x.data_ptr(), x.data_ptr(), 0, 5, x.stride(0), x.stride(1))
+    pool.ctx.rope3d_apply(0, 0, 0, 0, x.stride(0), x.stride(1))          # no pointers needed for nothing
+    torch.cuda.synchronize()
+    assert bool((x == 2.0).all())
 
 
 @pytest.mark.parametrize("mode", [BI, CA])
