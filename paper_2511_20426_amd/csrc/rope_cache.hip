@@ -20,6 +20,19 @@ namespace {
 
 struct alignas(16) U4 { uint32_t x, y, z, w; };
 
+// Tensors that pass through once (the unrotated inputs, the rotated output) are read and written
+// with the non-temporal hint, so that they do not displace the pool pages the attention kernel
+// re-reads from the caches.
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_nt;
+__device__ __forceinline__ U4 load_once(const void* p) {
+  const u32x4_nt t = __builtin_nontemporal_load(static_cast<const u32x4_nt*>(p));
+  return U4{t[0], t[1], t[2], t[3]};
+}
+__device__ __forceinline__ void store_once(void* p, const U4& a) {
+  const u32x4_nt t = {a.x, a.y, a.z, a.w};
+  __builtin_nontemporal_store(t, static_cast<u32x4_nt*>(p));
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
@@ -83,7 +96,7 @@ template <> struct Vec8<float> {
 template <> struct Vec8<uint16_t> {
   float v[8];
   __device__ void load(const uint16_t* p) {
-    const U4 a = *reinterpret_cast<const U4*>(p);
+    const U4 a = load_once(p);
     v[0] = bf16_lo(a.x); v[1] = bf16_hi(a.x); v[2] = bf16_lo(a.y); v[3] = bf16_hi(a.y);
     v[4] = bf16_lo(a.z); v[5] = bf16_hi(a.z); v[6] = bf16_lo(a.w); v[7] = bf16_hi(a.w);
   }
@@ -91,7 +104,7 @@ template <> struct Vec8<uint16_t> {
     U4 a;
     a.x = pack_bf16(v[0], v[1]); a.y = pack_bf16(v[2], v[3]);
     a.z = pack_bf16(v[4], v[5]); a.w = pack_bf16(v[6], v[7]);
-    *reinterpret_cast<U4*>(p) = a;
+    store_once(p, a);
   }
 };
 
@@ -284,7 +297,7 @@ __global__ __launch_bounds__(256) void cache_write_bf16_kernel(RopeGeom g, Paged
         rotate8(e, cs[i], sn[i]);
         kk.x = pack_bf16(e.v[0], e.v[1]); kk.y = pack_bf16(e.v[2], e.v[3]);
         kk.z = pack_bf16(e.v[4], e.v[5]); kk.w = pack_bf16(e.v[6], e.v[7]);
-        vv = *reinterpret_cast<const U4*>(a.v + src);
+        vv = load_once(a.v + src);
       }
       *reinterpret_cast<U4*>(kpage + r * 256 + ((c ^ (r & 15)) << 4)) = kk;
       uint32_t* row = vt + r * kVRowWords + c * 4;
