@@ -105,8 +105,9 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
     const int row = it * 4 + (lane >> 4), c = lane & 15;
     const u32x4 v = *reinterpret_cast<const u32x4*>(mine + row * kEpiRow + c * 16);
     const int gm = m0 + wm * 128 + row;
+    // the result passes through once: keep it from displacing the operand tiles in the caches
     if (gm < a.M)
-      *reinterpret_cast<u32x4*>(a.y + int64_t(gm) * a.ldy + n0 + wn * 128 + c * 8) = v;
+      __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(a.y + int64_t(gm) * a.ldy + n0 + wn * 128 + c * 8));
   }
 }
 
