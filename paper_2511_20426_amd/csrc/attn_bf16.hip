@@ -278,11 +278,17 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(AttnArgs a) {
 // variant 0: default; 1: no tail balancing (every work item walks its whole KV range)
 int32_t attn_bf16_variant_ok(int variant) { return variant == 0 || variant == 1 ? CA_OK : CA_EINVAL; }
 
-int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
-                         void* scratch, int max_partials, void* stream) {
+namespace {
+
+// Fills the kernel arguments for one forward.  Tail balancing: `capacity` partial results fit in
+// the scratch area; with adapt the split is reduced until the partials fit, without it the split
+// the device's CU count asks for is kept and *partials_needed tells the caller how many it takes.
+int32_t plan_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool, void* scratch,
+                       int capacity, bool adapt, AttnArgs* args, int* partials_needed) {
   if (p.head_dim != 128 || p.page_tokens != 128) return CA_EUNSUPPORTED;
   if (attn_bf16_variant_ok(variant) != CA_OK) return CA_EINVAL;
-  AttnArgs a{};
+  AttnArgs& a = *args;
+  a = AttnArgs{};
   a.q = static_cast<const uint16_t*>(q);
   a.o = static_cast<uint16_t*>(out);
   a.pool = static_cast<const uint8_t*>(pool);
@@ -326,17 +332,25 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
   a.full_items = a.work_per_xcd;
   a.partials = static_cast<float*>(scratch);
   const int rem = a.work_per_xcd % cus_per_xcd;
-  const int min_pages = p.n_vis[0] * p.pages_per_block;        // shortest KV walk of the launch
+  int min_vis = p.n_vis[0];                                    // shortest KV walk of the launch
+  for (int i = 1; i < p.n_q_blocks; ++i) min_vis = p.n_vis[i] < min_vis ? p.n_vis[i] : min_vis;
+  const int min_pages = min_vis * p.pages_per_block;
+  *partials_needed = 0;
   if (scratch && variant == 0 && rem > 0 && a.work_per_xcd > cus_per_xcd) {
     int split = cus_per_xcd / rem;
     if (split > 8) split = 8;
-    while (split > 1 && (min_pages < 8 * split || 8 * rem * split > max_partials)) --split;
+    while (split > 1 && (min_pages < 8 * split || (adapt && 8 * rem * split > capacity))) --split;
     if (split > 1) {
       a.split = split;
       a.split_items = rem;
       a.full_items = a.work_per_xcd - rem;
+      *partials_needed = 8 * rem * split;
     }
   }
+  return CA_OK;
+}
+
+int32_t enqueue_attn_bf16(const AttnArgs& a, void* stream) {
   const dim3 grid((unsigned)((a.full_items + a.split_items * a.split) * 8));
   if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void*>(attn_bf16_kernel), 4 * kPageBytes, 0);
       rc != CA_OK)
@@ -346,6 +360,17 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
     hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(8 * a.split_items)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), a);
   return finish_launch("attn_bf16.hip");
+}
+
+}  // namespace
+
+int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
+                         void* scratch, int max_partials, void* stream) {
+  AttnArgs a;
+  int needed = 0;
+  if (const int32_t rc = plan_attn_bf16(p, variant, q, out, pool, scratch, max_partials, true, &a, &needed); rc != CA_OK)
+    return rc;
+  return enqueue_attn_bf16(a, stream);
 }
 
 }  // namespace ca

@@ -21,21 +21,30 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _one_shot(w, mode, scale=None, seed=None, rows=None, heads=None, first_block=0, k_ramp=None):
-    """Cached blocks first_block..first_block+n_cached-1, in-flight ones right after."""
+def _one_shot(w, mode, scale=None, seed=None, rows=None, heads=None, first_block=0, k_ramp=None, bounded=False):
+    """Cached blocks first_block..first_block+n_cached-1, in-flight ones right after.  Returns the
+    GPU result and the oracle's as lists of per-block arrays; with bounded=True also the
+    per-element error bound (tests/_harness.py: attention_element_bound)."""
     q, k, v = W.draw_config(w, seed=seed, scale=scale, k_ramp=k_ramp)
     cached = list(range(first_block, first_block + w.n_cached))
     infl = list(range(first_block + w.n_cached, first_block + w.n_cached + w.n_inflight))
     pool = Hn.gpu_setup(w, k, v, cached, infl)
     out = Hn.gpu_forward(w, pool, q, infl, mode)
-    ref = Hn.oracle_forward(w, q, k, v, cached, infl, mode, rows=rows, heads=heads)
+    if bounded:
+        ref, bound = Hn.oracle_forward_bounded(w, q, k, v, cached, infl, mode, rows=rows, heads=heads)
+    else:
+        ref = Hn.oracle_forward(w, q, k, v, cached, infl, mode, rows=rows, heads=heads)
     L = w.block_tokens
     outs = W.split_blocks(out, L)
     if heads is not None:
         outs = [o[:, list(heads)] for o in outs]
     if rows is not None:
         outs = [o[np.asarray(r)] for o, r in zip(outs, rows)]
-    return outs, ref
+    return (outs, ref, bound) if bounded else (outs, ref)
+
+
+def _cat(xs):
+    return np.concatenate(xs)
 
 
 # --------------------------------------------------------------------------- fp32 path
@@ -213,15 +222,14 @@ def test_bf16_small_full_parity(mode, heads, gh, gw, nc, ni):
     w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=heads, grid_h=gh, grid_w=gw,
                         n_cached=nc, n_inflight=ni)
     _say(f"bf16 small heads={heads} grid={gh}x{gw} cached={nc} inflight={ni} mode={mode}")
-    outs, ref = _one_shot(w, mode, seed=21, first_block=2)
-    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", "small")
+    outs, ref, bound = _one_shot(w, mode, seed=21, first_block=2, bounded=True)
+    Hn.assert_close(_cat(outs), _cat(ref), "bf16", "small", bound=_cat(bound))
     # Peaked softmax (inputs x4: logits x16, V x4) so that a slip on a single key shows.  The
     # bf16 rounding of rotated Q and K perturbs a logit by about 2^-9 sqrt(2/3) sigma_q sigma_k
     # = 6e-3 here (4e-4 at the nominal scale), i.e. ~0.6 % on the dominant weights, on top of
     # the ~0.3 % from rounding P and O; outputs are 4x larger.  Bars scaled accordingly.
-    outs, ref = _one_shot(w, mode, seed=22, scale=2.0)
-    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", "small peaked",
-                    max_abs=0.12, rel=1.2e-2)
+    outs, ref, bound = _one_shot(w, mode, seed=22, scale=2.0, bounded=True)
+    Hn.assert_close(_cat(outs), _cat(ref), "bf16", "small peaked", max_abs=0.12, rel=1.2e-2, bound=_cat(bound))
 
 
 @pytest.mark.parametrize("mode", [BI, CA])
@@ -240,10 +248,14 @@ def test_bf16_moving_row_maximum(mode, ramp, bar):
     NaN, rows off by factors)."""
     w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=10, grid_w=13, n_cached=2, n_inflight=2)
     _say(f"bf16 moving row maximum ramp={ramp} mode={mode}")
-    outs, ref = _one_shot(w, mode, seed=31, k_ramp=ramp)
-    got, want = np.concatenate(outs), np.concatenate(ref)
+    outs, ref, bound = _one_shot(w, mode, seed=31, k_ramp=ramp, bounded=True)
+    got, want, bound = _cat(outs), _cat(ref), _cat(bound)
     assert np.isfinite(got).all()
-    Hn.assert_close(got, want, "bf16", f"moving maximum {ramp}", max_abs=bar * float(np.abs(want).max()) * 4, rel=bar)
+    # The per-element bound is first order in the logit perturbation: it applies while that stays
+    # well below 1 (the 24x ramps: ~5e-2); with logits of ~400 the rounding of K alone moves a
+    # logit by ~1 and only the norms are compared.
+    Hn.assert_close(got, want, "bf16", f"moving maximum {ramp}", max_abs=bar * float(np.abs(want).max()) * 4, rel=bar,
+                    bound=bound if bar <= 2e-2 else None)
 
 
 @pytest.mark.parametrize("gh,gw", [(3, 43), (3, 53), (10, 16), (7, 23), (12, 16), (223, 1), (14, 16), (15, 15),
@@ -256,8 +268,8 @@ def test_bf16_every_ragged_tail_class(gh, gw):
                         n_cached=1, n_inflight=2)
     _say(f"bf16 ragged tail class L={w.block_tokens} (mod 128 = {w.block_tokens % 128})")
     for mode in (BI, CA):
-        outs, ref = _one_shot(w, mode, seed=61, first_block=3)
-        Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", f"ragged L={w.block_tokens} mode={mode}")
+        outs, ref, bound = _one_shot(w, mode, seed=61, first_block=3, bounded=True)
+        Hn.assert_close(_cat(outs), _cat(ref), "bf16", f"ragged L={w.block_tokens} mode={mode}", bound=_cat(bound))
 
 
 @pytest.mark.parametrize("case", range(12))
@@ -275,8 +287,8 @@ def test_bf16_seeded_random_shapes(case):
                         n_cached=nc, n_inflight=ni)
     _say(f"random shape {case}: heads={heads} frames={fpb} grid={gh}x{gw} L={w.block_tokens} cached={nc} "
          f"inflight={ni} first={first} mode={mode}")
-    outs, ref = _one_shot(w, mode, seed=1000 + case, first_block=first)
-    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", f"random shape {case}")
+    outs, ref, bound = _one_shot(w, mode, seed=1000 + case, first_block=first, bounded=True)
+    Hn.assert_close(_cat(outs), _cat(ref), "bf16", f"random shape {case}", bound=_cat(bound))
 
 
 @pytest.mark.parametrize("case", range(24))
@@ -308,16 +320,16 @@ def test_bf16_seeded_random_shapes_wide(case):
     infl = list(range(first + nc, first + nc + ni))
     pool = Hn.gpu_setup(w, k, v, cached, infl)
     out = Hn.gpu_forward(w, pool, q, infl, mode)
-    ref = np.concatenate(Hn.oracle_forward(w, q, k, v, cached, infl, mode))
+    ref, bound = (_cat(x) for x in Hn.oracle_forward_bounded(w, q, k, v, cached, infl, mode))
     # logits grow with scale^2 and outputs with scale: the bars of the peaked variant, interpolated
     grow = (scale / 0.5) ** 1.3
-    Hn.assert_close(out, ref, "bf16", f"wide random shape {case}", max_abs=2e-2 * grow, rel=5e-3 * grow)
+    Hn.assert_close(out, ref, "bf16", f"wide random shape {case}", max_abs=2e-2 * grow, rel=5e-3 * grow, bound=bound)
     if ni > 1:
         f0 = int(rng.integers(0, ni))
         cnt = int(rng.integers(1, ni - f0 + 1))
         part = Hn.gpu_forward_share(w, pool, q, infl, mode, f0, cnt)
         Hn.assert_close(part, ref[f0 * L:(f0 + cnt) * L], "bf16", f"wide random shape {case} share ({f0},{cnt})",
-                        max_abs=2e-2 * grow, rel=5e-3 * grow)
+                        max_abs=2e-2 * grow, rel=5e-3 * grow, bound=bound[f0 * L:(f0 + cnt) * L])
 
 
 @pytest.mark.parametrize("mode", [BI, CA])
@@ -336,11 +348,15 @@ def test_share_of_a_forward_every_block_range(mode, dtype):
     infl = list(range(3 + w.n_cached, 3 + w.n_cached + w.n_inflight))
     pool = Hn.gpu_setup(w, k, v, cached, infl)
     whole = W.split_blocks(Hn.gpu_forward(w, pool, q, infl, mode), w.block_tokens)
-    ref = Hn.oracle_forward(w, q, k, v, cached, infl, mode)
+    if dtype == "bf16":
+        ref, bound = Hn.oracle_forward_bounded(w, q, k, v, cached, infl, mode)
+    else:
+        ref, bound = Hn.oracle_forward(w, q, k, v, cached, infl, mode), None
     for first in range(w.n_inflight):
         for count in range(1, w.n_inflight - first + 1):
             part = Hn.gpu_forward_share(w, pool, q, infl, mode, first, count)
-            Hn.assert_close(part, np.concatenate(ref[first:first + count]), dtype, f"share ({first},{count})")
+            Hn.assert_close(part, _cat(ref[first:first + count]), dtype, f"share ({first},{count})",
+                            bound=None if bound is None else _cat(bound[first:first + count]))
             same = np.concatenate(whole[first:first + count])
             if dtype == "bf16":
                 keys = (w.n_cached + (first + 1 if mode == CA else w.n_inflight)) * w.block_tokens
@@ -357,8 +373,8 @@ def test_bf16_largest_configuration(mode, gh, gw):
     w = W.small_variant(W.CONFIGS["c5_wan1p3b_rollout"], heads=2, grid_h=gh, grid_w=gw, window_blocks=23,
                         max_inflight=8, n_cached=24, n_inflight=8)
     _say(f"largest configuration grid={gh}x{gw} mode={mode}")
-    outs, ref = _one_shot(w, mode, seed=71)
-    Hn.assert_close(np.concatenate(outs), np.concatenate(ref), "bf16", "32 KV blocks, 8 in flight")
+    outs, ref, bound = _one_shot(w, mode, seed=71, bounded=True)
+    Hn.assert_close(_cat(outs), _cat(ref), "bf16", "32 KV blocks, 8 in flight", bound=_cat(bound))
 
 
 def test_bf16_single_block_modes_agree_bitwise():
@@ -456,67 +472,86 @@ def _reordering_bound(a, b, v, keys):
     return 2.0 ** -7 * np.maximum(np.abs(a), np.abs(b)) + 8 * 2.0 ** -9 * v_rms / np.sqrt(keys)
 
 
-def _full_shape(name, modes, heads_sample, n_random, shares=()):
+def _parity_rows(L, i, n_random, seed):
+    """Rows of in-flight block i that meet the oracle at the full shapes: the first and last two
+    (the last ones sit in the ragged tile: 4680 = 18 * 256 + 72), both sides of every multiple of
+    128 rows -- every edge of a 256-row workgroup tile and the middle of each tile, where its
+    second pair of waves starts -- in either tiling (tiles counted from the block's first row in
+    a block-causal launch, from the first row of the whole batch in a bidirectional one), and
+    n_random seeded rows."""
+    return W.sample_rows(L, n_random, seed=seed, tile_edges=(128,), offsets=(0, (i * L) % 256))
+
+
+def _full_shape(name, modes, n_random=16, shares=(), scale=None, full=False, bars=None, reorder_checks=True):
+    """One forward at a configuration's full shape against the oracle on every head: all rows
+    (full=True) or the rows of _parity_rows; norm bars plus the per-element bound."""
     w = W.CONFIGS[name]
     t0 = time.time()
-    q, k, v = W.draw_config(w)
+    q, k, v = W.draw_config(w, scale=scale)
     _say(f"{name}: drew inputs in {time.time() - t0:.1f}s")
     cached = list(range(w.n_cached))
     infl = list(range(w.n_cached, w.n_cached + w.n_inflight))
     pool = Hn.gpu_setup(w, k, v, cached, infl, timesteps=list(W.TIMESTEPS[::-1][:len(infl)]))
     L = w.block_tokens
-    rows = [W.sample_rows(L, n_random, seed=100 + i, tile_edges=(1536,)) for i in range(len(infl))]
+    rows = None if full else [_parity_rows(L, i, n_random, seed=100 + i) for i in range(len(infl))]
+    bars = bars or {}
     for mode in modes:
         t0 = time.time()
         out = Hn.gpu_forward(w, pool, q, infl, mode)
         _say(f"{name}: gpu forward mode={mode} done in {time.time() - t0:.1f}s")
         t0 = time.time()
-        ref = Hn.oracle_forward(w, q, k, v, cached, infl, mode, rows=rows, heads=heads_sample)
-        _say(f"{name}: oracle on {sum(len(r) for r in rows)} rows x {len(heads_sample)} heads in {time.time() - t0:.1f}s")
-        got = [o[np.asarray(r)][:, list(heads_sample)] for o, r in zip(W.split_blocks(out, L), rows)]
-        Hn.assert_close(np.concatenate(got), np.concatenate(ref), "bf16", f"{name} mode={mode}")
-        # properties that hold for every row at any size: outputs are convex combinations of V rows,
-        # and cutting the KV walk of the last work items into page ranges (tail balancing, merged
-        # afterwards) changes a result only through rounding
+        ref, bound = Hn.oracle_forward_bounded(w, q, k, v, cached, infl, mode, rows=rows)
+        n_rows = len(infl) * L if full else sum(len(r) for r in rows)
+        _say(f"{name}: oracle on {n_rows} rows x {w.heads} heads in {time.time() - t0:.1f}s")
+        got = W.split_blocks(out, L) if full else [o[r] for o, r in zip(W.split_blocks(out, L), rows)]
+        Hn.assert_close(_cat(got), _cat(ref), "bf16", f"{name} mode={mode}", bound=_cat(bound), **bars)
         assert np.isfinite(out).all()
-        assert np.abs(out).max() <= np.abs(W.bf16_bits_to_f32(v)).max()
-        pool.ctx.set_kernel_variant(1)
-        whole = Hn.gpu_forward(w, pool, q, infl, mode)
-        pool.ctx.set_kernel_variant(0)
-        gap = np.abs(out - whole)
-        _say(f"{name}: split vs whole KV walks: {int((gap > 0).sum())} of {gap.size} elements differ, "
-             f"max {float(gap.max()):.2e}")
-        keys = (w.n_cached + (1 if mode == CA else w.n_inflight)) * L
-        bad = np.argwhere(gap > _reordering_bound(out, whole, v, keys))
-        if len(bad):
-            i = tuple(bad[0])
-            _say(f"{name}: {len(bad)} outside the bound, first at {i}: {out[i]!r} vs {whole[i]!r}")
-        assert len(bad) == 0
+        assert np.abs(out).max() <= np.abs(W.bf16_bits_to_f32(v)).max()     # convex combinations of V rows
+        if reorder_checks:
+            # cutting the KV walk of the last work items into page ranges (tail balancing, merged
+            # afterwards) changes a result only through rounding: every element, GPU against GPU
+            pool.ctx.set_kernel_variant(1)
+            whole = Hn.gpu_forward(w, pool, q, infl, mode)
+            pool.ctx.set_kernel_variant(0)
+            gap = np.abs(out - whole)
+            _say(f"{name}: split vs whole KV walks: {int((gap > 0).sum())} of {gap.size} elements differ, "
+                 f"max {float(gap.max()):.2e}")
+            keys = (w.n_cached + (1 if mode == CA else w.n_inflight)) * L
+            bad = np.argwhere(gap > _reordering_bound(out, whole, v, keys))
+            if len(bad):
+                i = tuple(bad[0])
+                _say(f"{name}: {len(bad)} outside the bound, first at {i}: {out[i]!r} vs {whole[i]!r}")
+            assert len(bad) == 0
         # one device's share of the forward (queries of some in-flight blocks only): same rows,
         # tiled from the share's first row instead of the batch's
         for first, count in shares:
             part = Hn.gpu_forward_share(w, pool, q, infl, mode, first, count)
-            ref_rows = out[first * L:(first + count) * L]
-            keys_s = (w.n_cached + (first + 1 if mode == CA else w.n_inflight)) * L
-            gap = np.abs(part - ref_rows)
-            _say(f"{name}: share ({first},{count}) mode={mode} vs whole forward: max {float(gap.max()):.2e}")
-            assert (gap <= _reordering_bound(part, ref_rows, v, keys_s)).all()
-            got = [o[np.asarray(r)][:, list(heads_sample)]
-                   for o, r in zip(W.split_blocks(part, L), rows[first:first + count])]
-            Hn.assert_close(np.concatenate(got), np.concatenate(ref[first:first + count]), "bf16",
-                            f"{name} share ({first},{count}) mode={mode}")
+            got = [o[r] for o, r in zip(W.split_blocks(part, L), rows[first:first + count])]
+            Hn.assert_close(_cat(got), _cat(ref[first:first + count]), "bf16",
+                            f"{name} share ({first},{count}) mode={mode}", bound=_cat(bound[first:first + count]), **bars)
+    return pool
 
 
-def test_c2_wan1p3b_sequential_sampled():
-    _full_shape("c2_wan1p3b_seq", [BI], heads_sample=range(12), n_random=16)
+def test_c2_wan1p3b_sequential_full_tensor():
+    """Wan-1.3B shape, one block in flight on a 6-block cache: every output element (4680 rows x
+    12 heads x 128) against the oracle."""
+    _full_shape("c2_wan1p3b_seq", [BI], full=True)
 
 
-def test_c3_wan1p3b_cascade_both_modes_sampled():
-    _full_shape("c3_wan1p3b_cascade5", [BI, CA], heads_sample=(0, 5, 11), n_random=12, shares=((0, 1), (3, 2)))
+def test_c2_wan1p3b_sequential_full_tensor_peaked():
+    """The same shape with inputs x4 (logits x16, V x4): a softmax over 32760 keys that a few keys
+    dominate, so that one missing or misplaced key would show.  Norm bars as for the small peaked
+    cases (test_bf16_small_full_parity), per-element bound from the same error model."""
+    _full_shape("c2_wan1p3b_seq", [BI], full=True, scale=2.0, bars=dict(max_abs=0.12, rel=1.2e-2),
+                reorder_checks=False)
 
 
-def test_c4_wan14b_cascade_sampled():
-    _full_shape("c4_wan14b_cascade5", [BI], heads_sample=(0, 1, 17, 39), n_random=8, shares=((2, 1),))
+def test_c3_wan1p3b_cascade_both_modes_all_heads():
+    _full_shape("c3_wan1p3b_cascade5", [BI, CA], shares=((0, 1), (3, 2)))
+
+
+def test_c4_wan14b_cascade_all_heads():
+    _full_shape("c4_wan14b_cascade5", [BI], shares=((2, 1),))
 
 
 # --------------------------------------------------------------------------- long rollout (ring buffer)
@@ -525,8 +560,9 @@ def test_c5_rollout_ring_buffer():
     """40 cascade steps at the Wan-1.3B shape: 1 sink + 6-block window + 5 in flight, evict and
     append every step, prompt switch (re-tag) at step 20.  Slot of every append, snapshot,
     visibility and page indices are compared bit-exact with the oracle at every step; outputs are
-    compared numerically on sampled rows at steps that cover ramp-up, the first full cascade,
-    the first wrapped ring, the switch and the end."""
+    compared numerically, on every head and on the rows of _parity_rows, at steps that cover
+    ramp-up (0, 3), the first full cascade (4), the first wrapped ring (11, block-causal), the
+    steps around the prompt switch (19, 20, 21) and the end (39)."""
     import torch
     from paper_2511_20426_amd.runner import CascadePool
     from paper_2511_20426_amd import binding as B
@@ -534,8 +570,7 @@ def test_c5_rollout_ring_buffer():
     L, H, D, C = w.block_tokens, w.heads, w.head_dim, w.max_inflight
     pool = CascadePool.for_workload(w)
     cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, C, w.pages_per_block, H)
-    checked = (0, 3, 4, 11, 20, 39)
-    heads_sample = (0, 7, 11)
+    checked = (0, 3, 4, 11, 19, 20, 21, 39)
     # which (step, position) draws the oracle will need: in-flight data of checked steps, and the
     # last write (the tc step, position 0) of every block that is cached at a checked step
     need = set()
@@ -593,22 +628,15 @@ def test_c5_rollout_ring_buffer():
         if step in checked:
             torch.cuda.synchronize()
             got = Hn.from_torch(out, w.dtype)
-            pos = lambda g: orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w)
-            hs = list(heads_sample)
             kb, vb = [], []
             for g, st in zip(order, states):
-                if st == orc.NOISY:
-                    k, v = host[(step, infl.index(g))][1:]
-                else:
-                    k, v = final_kv[g]
-                kb.append(orc.rope3d(W.to_f64(k[:, hs]), pos(g), w.rope_dims, w.rope_theta))
-                vb.append(W.to_f64(v[:, hs]))
-            rows = [W.sample_rows(L, 6, seed=step * 10 + i, tile_edges=(2304,)) for i in range(len(infl))]
-            qb = [orc.rope3d(W.to_f64(host[(step, i)][0][:, hs]), pos(g), w.rope_dims, w.rope_theta)[rows[i]]
-                  for i, g in enumerate(infl)]
-            ref = orc.cascade_attention(qb, kb, vb, orc.visibility(states, order, infl, mode))
-            gsel = [got[i * L:(i + 1) * L][rows[i]][:, hs] for i in range(len(infl))]
-            Hn.assert_close(np.concatenate(gsel), np.concatenate(ref), "bf16", f"rollout step {step}")
+                k, v = host[(step, infl.index(g))][1:] if st == orc.NOISY else final_kv[g]
+                kb.append(k); vb.append(v)
+            rows = [_parity_rows(L, i, 16, seed=step * 10 + i) for i in range(len(infl))]
+            ref, bound = Hn.oracle_forward_bounded(w, [host[(step, i)][0] for i in range(len(infl))], None, None, None,
+                                                   infl, mode, rows=rows, kv=(order, states, kb, vb))
+            gsel = [got[i * L:(i + 1) * L][rows[i]] for i in range(len(infl))]
+            Hn.assert_close(_cat(gsel), _cat(ref), "bf16", f"rollout step {step}", bound=_cat(bound))
             _say(f"rollout step {step}: {len(infl)} in flight, {len(order)} KV blocks, t={time.time() - t_start:.1f}s")
         if batch[0][1] == 0:
             pool.ctx.kv_cache_promote(b)
@@ -657,9 +685,7 @@ def test_algorithm1_rollout_driver(mode, lag, sink, window):
         trace = [(batch[0][0], batch[0][1], len(batch) - 1, batch) for batch in orc.cascade_type_schedule(n_blocks, 5, lag)]
         assert len(trace) == lag * (n_blocks - 1) + 5
     cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, w.max_inflight, w.pages_per_block, H)
-    pos = lambda g: orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w)
     final_kv = {}
-    worst = 0.0
     for it, (b, tau, d, batch) in enumerate(trace):
         rec = ro.step()
         torch.cuda.synchronize()
@@ -673,13 +699,11 @@ def test_algorithm1_rollout_driver(mode, lag, sink, window):
         kb, vb = [], []
         for g, st in zip(order, states):
             k, v = host[(it, infl.index(g))][1:] if st == orc.NOISY else final_kv[g]
-            kb.append(orc.rope3d(W.to_f64(k), pos(g), w.rope_dims, w.rope_theta))
-            vb.append(W.to_f64(v))
-        qb = [orc.rope3d(W.to_f64(host[(it, i)][0]), pos(g), w.rope_dims, w.rope_theta)
-              for i, g in enumerate(infl)]
-        ref = orc.cascade_attention(qb, kb, vb, orc.visibility(states, order, infl, mode))
+            kb.append(k); vb.append(v)
+        ref, bound = Hn.oracle_forward_bounded(w, [host[(it, i)][0] for i in range(len(infl))], None, None, None,
+                                               infl, mode, kv=(order, states, kb, vb))
         got = np.concatenate(outs[it])
-        Hn.assert_close(got, np.concatenate(ref), "bf16", f"alg1 iteration {it}")
+        Hn.assert_close(got, _cat(ref), "bf16", f"alg1 iteration {it}", bound=_cat(bound))
         evicted = orc.rollout_finish(cache, b, [(g, W.TIMESTEPS[ti]) for g, ti in batch])
         assert rec.completed == (b if tau == 4 else -1)
         assert rec.evicted == (-1 if evicted is None else evicted)

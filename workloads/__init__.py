@@ -183,13 +183,16 @@ def split_blocks(x: np.ndarray, L: int) -> List[np.ndarray]:
     return [x[i * L:(i + 1) * L] for i in range(x.shape[0] // L)]
 
 
-def sample_rows(L: int, n_random: int, seed: int, tile_edges=(128, 256)) -> np.ndarray:
+def sample_rows(L: int, n_random: int, seed: int, tile_edges=(128, 256), offsets=(0,)) -> np.ndarray:
     """Deterministic row sample inside one block: first/last two rows, rows either
-    side of every multiple of the given tile sizes, plus seeded random rows."""
+    side of every multiple of the given tile sizes, plus seeded random rows.  `offsets`: where
+    tiles start relative to the block's first row (0: tiles counted from the block's own first
+    row; o: from a row o before it, as when tiles run across several blocks laid end to end)."""
     rows = {0, 1, L - 2, L - 1}
     for t in tile_edges:
-        for e in range(t, L, t):
-            rows.update((e - 1, e))
+        for off in offsets:
+            for e in range(t - off % t, L, t):
+                rows.update((e - 1, e))
     rng = np.random.default_rng(seed)
     rows.update(int(r) for r in rng.integers(0, L, size=n_random))
     return np.array(sorted(r for r in rows if 0 <= r < L), dtype=np.int64)
