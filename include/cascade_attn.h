@@ -66,7 +66,8 @@ enum {
   CA_ESTATE = -4,       /* wrong state: evict a sink, promote a clean block, rewrite a clean */
   CA_EUNSUPPORTED = -5, /* dtype / head_dim / page size the kernels do not cover             */
   CA_ENOPOOL = -6,      /* device work asked of a metadata-only context                      */
-  CA_EDEVICE = -7       /* the HIP runtime refused a launch                                  */
+  CA_EDEVICE = -7,      /* the HIP runtime refused a launch                                  */
+  CA_ETOOBIG = -8       /* cascade_attn_forward_static: more partial tiles than its area holds */
 };
 
 enum { CA_F32 = 0, CA_BF16 = 1 };
@@ -181,6 +182,27 @@ int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev,
                                    const int64_t* inflight_block_ids, int32_t n_inflight,
                                    int32_t first, int32_t count, int32_t mode, void* out_dev,
                                    void* hip_stream);
+
+/* cascade_attn_forward for callers that can neither allocate device memory nor spare any of their
+ * own for the library's intermediate results: code recorded into a HIP graph by a harness that owns
+ * every allocation, tight serving loops, hosts that forbid hipMalloc after start-up.  Arguments,
+ * checks, kernels and results are those of cascade_attn_forward (bit for bit on a device with at
+ * most 32 CUs per XCD); the one difference is where the partial results of split KV walks go: not
+ * the area at the end of the caller's pool but a static device array inside this library, 256
+ * partial tiles = 34.6 MB, which every GPU the library runs on holds from the moment the library is
+ * loaded on it until the process ends.  The call allocates nothing, frees nothing, copies nothing
+ * and sets no memory: it enqueues the same kernel launches.  Nothing in the area has to start at
+ * zero (every partial tile is written in full before it is read), and it keeps the last call's
+ * contents.  All contexts of a process share one area per GPU: static-scratch forwards that overlap
+ * on one GPU (different streams, or different contexts) race and must be ordered by the caller.
+ * A forward whose split would need more than 256 partial tiles (possible only on a device with
+ * more than 32 CUs per XCD) is refused with CA_ETOOBIG and nothing is enqueued.  The first call on
+ * a device (or ca_create with a pool while that device is current) looks up the area's address
+ * there and sets the kernel attribute; make it outside stream capture.  fp32 contexts use no
+ * scratch at all: for them this is cascade_attn_forward. */
+int32_t cascade_attn_forward_static(ca_ctx* ctx, const void* q_dev,
+                                    const int64_t* inflight_block_ids, int32_t n_inflight,
+                                    int32_t mode, void* out_dev, void* hip_stream);
 
 /* The mask cascade_attn_forward would use: vis[i*n_kv + r] in {0,1} for query block i and
  * KV block r of the KV sequence, kv_block_ids[r] its block id.  cap = capacity of

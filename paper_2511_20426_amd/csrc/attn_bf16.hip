@@ -29,6 +29,8 @@
 //   hand-scheduled assembly emitted by gen_attn_core.py.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
+
 #include "ca_internal.hpp"
 
 namespace ca {
@@ -283,7 +285,7 @@ namespace {
 // Fills the kernel arguments for one forward.  Tail balancing: `capacity` partial results fit in
 // the scratch area; with adapt the split is reduced until the partials fit, without it the split
 // the device's CU count asks for is kept and *partials_needed tells the caller how many it takes.
-int32_t plan_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool, void* scratch,
+int32_t plan_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool, void* partials_dev,
                        int capacity, bool adapt, AttnArgs* args, int* partials_needed) {
   if (p.head_dim != 128 || p.page_tokens != 128) return CA_EUNSUPPORTED;
   if (attn_bf16_variant_ok(variant) != CA_OK) return CA_EINVAL;
@@ -330,13 +332,13 @@ int32_t plan_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out,
   a.split = 1;
   a.split_items = 0;
   a.full_items = a.work_per_xcd;
-  a.partials = static_cast<float*>(scratch);
+  a.partials = static_cast<float*>(partials_dev);
   const int rem = a.work_per_xcd % cus_per_xcd;
   int min_vis = p.n_vis[0];                                    // shortest KV walk of the launch
   for (int i = 1; i < p.n_q_blocks; ++i) min_vis = p.n_vis[i] < min_vis ? p.n_vis[i] : min_vis;
   const int min_pages = min_vis * p.pages_per_block;
   *partials_needed = 0;
-  if (scratch && variant == 0 && rem > 0 && a.work_per_xcd > cus_per_xcd) {
+  if (partials_dev && variant == 0 && rem > 0 && a.work_per_xcd > cus_per_xcd) {
     int split = cus_per_xcd / rem;
     if (split > 8) split = 8;
     while (split > 1 && (min_pages < 8 * split || (adapt && 8 * rem * split > capacity))) --split;
@@ -365,11 +367,60 @@ int32_t enqueue_attn_bf16(const AttnArgs& a, void* stream) {
 }  // namespace
 
 int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
-                         void* scratch, int max_partials, void* stream) {
+                         void* partials_dev, int max_partials, void* stream) {
   AttnArgs a;
   int needed = 0;
-  if (const int32_t rc = plan_attn_bf16(p, variant, q, out, pool, scratch, max_partials, true, &a, &needed); rc != CA_OK)
+  if (const int32_t rc = plan_attn_bf16(p, variant, q, out, pool, partials_dev, max_partials, true, &a, &needed);
+      rc != CA_OK)
     return rc;
+  return enqueue_attn_bf16(a, stream);
+}
+
+// ---- the same launch with the partial results in device memory this library holds itself, for
+// callers that cannot hand over or allocate any: a file-scope array, one copy per GPU, which
+// stays with the process.  Host code never uses the array's name as an address: the address on
+// the current device is looked up once per device and kept.
+namespace {
+
+constexpr int kStaticPartials = 256;      // 256 tiles x 256 rows x 132 floats = 34.6 MB per GPU
+static __device__ __align__(256) float scratch[size_t(kStaticPartials) * kPartialFloats];
+
+std::atomic<float*> g_static_scratch[kMaxDevices];
+
+int32_t static_scratch_on_current_device(float** out) {
+  int dev = 0;
+  if (const hipError_t e = hipGetDevice(&dev); e != hipSuccess) return device_failure("hipGetDevice", e);
+  if (dev < 0 || dev >= kMaxDevices) return CA_EUNSUPPORTED;
+  float* ptr = g_static_scratch[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    void* sym = nullptr;
+    if (const hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)); e != hipSuccess || !sym)
+      return device_failure("hipGetSymbolAddress(scratch)", e);
+    ptr = static_cast<float*>(sym);
+    g_static_scratch[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return CA_OK;
+}
+
+}  // namespace
+
+void attn_static_scratch_prepare() {
+  float* ptr = nullptr;
+  if (static_scratch_on_current_device(&ptr) != CA_OK) (void)hipGetLastError();   // the entry point will try again
+}
+
+int32_t launch_attn_bf16_static(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
+                                void* stream) {
+  float* ptr = nullptr;
+  if (const int32_t rc = static_scratch_on_current_device(&ptr); rc != CA_OK) return rc;
+  AttnArgs a;
+  int needed = 0;
+  // the split the device's CU count asks for, as launch_attn_bf16 takes it when its area is large
+  // enough; what does not fit the static area is refused, not shrunk
+  if (const int32_t rc = plan_attn_bf16(p, variant, q, out, pool, ptr, kStaticPartials, false, &a, &needed); rc != CA_OK)
+    return rc;
+  if (needed > kStaticPartials) return CA_ETOOBIG;
   return enqueue_attn_bf16(a, stream);
 }
 

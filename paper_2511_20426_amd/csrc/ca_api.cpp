@@ -54,6 +54,7 @@ int32_t ca_create(const ca_config* cfg, void* pool_dev, size_t pool_bytes, ca_ct
   }
   ctx->pool = pool_dev;
   ctx->pool_bytes = pool_bytes;
+  if (pool_dev && cfg->dtype == CA_BF16) ca::attn_static_scratch_prepare();   // for cascade_attn_forward_static
   *out = ctx;
   return CA_OK;
 }
@@ -158,15 +159,15 @@ int32_t rope3d_apply(const ca_ctx* ctx, const void* x_dev, void* y_dev, int64_t 
                               first_frame, hip_stream);
 }
 
-int32_t cascade_attn_forward(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,
-                             int32_t n_inflight, int32_t mode, void* out_dev, void* hip_stream) {
-  return cascade_attn_forward_share(ctx, q_dev, inflight_block_ids, n_inflight, 0, n_inflight, mode, out_dev,
-                                    hip_stream);
-}
+}  // extern "C"
 
-int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,
-                                   int32_t n_inflight, int32_t first, int32_t count, int32_t mode,
-                                   void* out_dev, void* hip_stream) {
+namespace {
+
+// partials: where the bf16 kernel's split work items put their partial results
+enum class Partials { kInPool, kStatic };
+
+int32_t forward_impl(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids, int32_t n_inflight,
+                     int32_t first, int32_t count, int32_t mode, void* out_dev, void* hip_stream, Partials where) {
   if (!ctx) return CA_EINVAL;
   const ca::CacheMeta& m = ctx->meta;
   std::vector<int64_t> ids;
@@ -191,11 +192,34 @@ int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev, const int64_t
     p.n_vis[i] = n_vis[first + i];
     if (p.n_vis[i] != p.n_vis[0]) p.uniform = 0;
   }
-  if (c.dtype == CA_BF16)
-    return ca::launch_attn_bf16(p, ctx->variant, q_dev, out_dev, ctx->pool,
-                                static_cast<uint8_t*>(ctx->pool) + m.page_bytes_total(), ca::kMaxPartials,
-                                hip_stream);
-  return ca::launch_attn_f32(p, q_dev, out_dev, ctx->pool, hip_stream);
+  if (c.dtype != CA_BF16) return ca::launch_attn_f32(p, q_dev, out_dev, ctx->pool, hip_stream);   // no scratch at all
+  if (where == Partials::kStatic)
+    return ca::launch_attn_bf16_static(p, ctx->variant, q_dev, out_dev, ctx->pool, hip_stream);
+  return ca::launch_attn_bf16(p, ctx->variant, q_dev, out_dev, ctx->pool,
+                              static_cast<uint8_t*>(ctx->pool) + m.page_bytes_total(), ca::kMaxPartials, hip_stream);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t cascade_attn_forward(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,
+                             int32_t n_inflight, int32_t mode, void* out_dev, void* hip_stream) {
+  return forward_impl(ctx, q_dev, inflight_block_ids, n_inflight, 0, n_inflight, mode, out_dev, hip_stream,
+                      Partials::kInPool);
+}
+
+int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,
+                                   int32_t n_inflight, int32_t first, int32_t count, int32_t mode,
+                                   void* out_dev, void* hip_stream) {
+  return forward_impl(ctx, q_dev, inflight_block_ids, n_inflight, first, count, mode, out_dev, hip_stream,
+                      Partials::kInPool);
+}
+
+int32_t cascade_attn_forward_static(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,
+                                    int32_t n_inflight, int32_t mode, void* out_dev, void* hip_stream) {
+  return forward_impl(ctx, q_dev, inflight_block_ids, n_inflight, 0, n_inflight, mode, out_dev, hip_stream,
+                      Partials::kStatic);
 }
 
 int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids,
@@ -246,6 +270,7 @@ const char* ca_strerror(int32_t code) {
     case CA_EUNSUPPORTED: return "dtype / head_dim / page size not supported";
     case CA_ENOPOOL: return "context has no device pool";
     case CA_EDEVICE: return "HIP launch failed";
+    case CA_ETOOBIG: return "the forward needs more partial-result tiles than the static scratch area holds";
     default: return "unknown error";
   }
 }

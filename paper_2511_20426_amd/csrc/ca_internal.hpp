@@ -97,6 +97,14 @@ int32_t launch_attn_f32(const AttnPlan& p, const void* q, void* out, const void*
 int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
                          void* scratch, int max_partials, void* stream);
 int32_t attn_bf16_variant_ok(int variant);
+// The same launch with the partial results in the library's own static device array (one copy per
+// GPU, kept for the life of the process) instead of caller memory; CA_ETOOBIG if the split the
+// device asks for needs more partial tiles than that array holds.  attn_static_scratch_prepare
+// looks the array's address up for the current device ahead of the first launch (errors ignored:
+// the launch looks again).
+int32_t launch_attn_bf16_static(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
+                                void* stream);
+void attn_static_scratch_prepare();
 
 // Launchers end with this: CA_OK, or CA_EDEVICE after recording the HIP error text.
 int32_t run_mfma_microbench(int data_kind, int trips, void* scratch, size_t scratch_bytes, void* stream,
@@ -109,6 +117,7 @@ constexpr int kMaxDevices = 64;
 int32_t device_cu_count(int* n_cu);                                   // of the current device
 int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot);  // slot: 0 attention, 1 GEMM
 int32_t finish_launch(const char* what);
+int32_t device_failure(const char* what, int hip_error);   // records the text, clears HIP's last error, returns CA_EDEVICE
 const char* last_device_error();
 
 }  // namespace ca

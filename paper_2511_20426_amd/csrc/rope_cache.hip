@@ -338,6 +338,12 @@ int32_t finish_launch(const char* what) {
   return CA_EDEVICE;
 }
 
+int32_t device_failure(const char* what, int hip_error) {
+  (void)hipGetLastError();
+  snprintf(g_last_error, sizeof(g_last_error), "%s: %s", what, hipGetErrorString(static_cast<hipError_t>(hip_error)));
+  return CA_EDEVICE;
+}
+
 const char* last_device_error() { return g_last_error; }
 
 namespace {

@@ -81,15 +81,21 @@ class CascadePool:
         return y
 
     def forward(self, q_rot: torch.Tensor, inflight: Sequence[int], mode: int,
-                out: torch.Tensor | None = None, share: tuple[int, int] | None = None) -> torch.Tensor:
+                out: torch.Tensor | None = None, share: tuple[int, int] | None = None,
+                static_scratch: bool = False) -> torch.Tensor:
         """Attention of the in-flight blocks' queries; with share = (first, count) only of blocks
-        first .. first+count-1 of `inflight` (q_rot and the result then hold just those)."""
+        first .. first+count-1 of `inflight` (q_rot and the result then hold just those);
+        static_scratch: through cascade_attn_forward_static (`out` must then be given: that call
+        is for callers that do not allocate)."""
         self._check(q_rot)
         n_q = len(inflight) if share is None else share[1]
         assert q_rot.is_contiguous() and q_rot.shape[0] == n_q * self.block_tokens
         o = torch.empty_like(q_rot) if out is None else out
         assert o.is_contiguous() and o.shape == q_rot.shape
-        if share is None:
+        if static_scratch:
+            assert share is None and out is not None
+            self.ctx.cascade_attn_forward_static(q_rot.data_ptr(), list(inflight), mode, o.data_ptr(), self._stream())
+        elif share is None:
             self.ctx.cascade_attn_forward(q_rot.data_ptr(), list(inflight), mode, o.data_ptr(), self._stream())
         else:
             self.ctx.cascade_attn_forward_share(q_rot.data_ptr(), list(inflight), share[0], share[1], mode,

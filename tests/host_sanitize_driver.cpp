@@ -42,6 +42,11 @@ int32_t launch_attn_bf16(const AttnPlan& p, int, const void* q, void* out, const
     if (p.kv_slot[i] < 0) return CA_EDEVICE;
   return q && out && pool && scratch && max_partials > 0 ? CA_OK : CA_EDEVICE;
 }
+int32_t launch_attn_bf16_static(const AttnPlan& p, int, const void* q, void* out, const void* pool, void*) {
+  ++g_launches;
+  return q && out && pool && p.n_q_blocks > 0 ? CA_OK : CA_EDEVICE;
+}
+void attn_static_scratch_prepare() {}
 int32_t attn_bf16_variant_ok(int variant) { return variant == 0 || variant == 1 ? CA_OK : CA_EINVAL; }
 int32_t run_mfma_microbench(int, int, void*, size_t, void*, double*, double*) { return CA_OK; }
 int32_t launch_gemm_bf16(const void*, const void*, void*, int64_t, int32_t n, int32_t k, int64_t, int64_t, int64_t,
@@ -109,6 +114,8 @@ static void rollout(int dtype, int sink, int window, int lag) {
     for (int mode = 0; mode < 2; ++mode) {
       CHECK(cascade_attn_forward(ctx, tensor, ids, n, mode, tensor, nullptr) == CA_OK);
       CHECK(cascade_attn_forward_share(ctx, tensor, ids, n, n - 1, 1, mode, tensor, nullptr) == CA_OK);
+      CHECK(cascade_attn_forward_static(ctx, tensor, ids, n, mode, tensor, nullptr) == CA_OK);
+      CHECK(cascade_attn_forward_static(ctx, nullptr, ids, n, mode, tensor, nullptr) == CA_EINVAL);
       CHECK(cascade_attn_forward_share(ctx, tensor, ids, n, n, 1, mode, tensor, nullptr) == CA_EINVAL);
       uint8_t vis[8 * 32];
       int64_t kv_ids[32];
