@@ -141,8 +141,10 @@ int32_t kv_cache_retag(ca_ctx* ctx, int32_t new_prompt_epoch);
  * it exceeds cap (then only cap entries are written). */
 int32_t kv_cache_snapshot(const ca_ctx* ctx, ca_slot_info* out, int32_t cap, int32_t* n_out);
 
-/* Physical page-pair number of (block, page, head), the rule stated above; CA_ENOENT if the
- * block is not resident. */
+/* Physical page-pair number of (block, page, head), the rule stated above under "Pool layout";
+ * CA_ENOENT if the block is not resident.  The paper fixes no placement (Sec. 3.3 only asks for one
+ * pool that every block reads, a rolling window and a sink): the rule is this library's own and is
+ * exposed so that a caller -- or a test -- can find a block's bytes. */
 int32_t kv_cache_page_index(const ca_ctx* ctx, int64_t block_id, int32_t page, int32_t head,
                             int64_t* index_out);
 
@@ -211,12 +213,11 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
                             int32_t n_inflight, int32_t mode, uint8_t* vis,
                             int64_t* kv_block_ids, int32_t cap, int32_t* n_kv_out);
 
-/* Selects an attention kernel variant for experiments: 0 = default, 1 = no tail balancing (every
- * workgroup walks its whole KV range).  Unknown values are rejected with CA_EINVAL. */
-int32_t ca_set_kernel_variant(ca_ctx* ctx, int32_t variant);
-
 /* ---- The linear maps either side of the attention inside a layer (QKV projection before it,
- * output projection after it): y[m][n] = sum_k x[m][k] * w[n][k], bf16 in and out, fp32
+ * output projection after it).  The paper takes the generator G_theta as given (Sec. 3.1) and says
+ * nothing of its layers; the reading taken here is the plain one: no bias, no q/k normalisation,
+ * weights stored [out, in], QKV output rows ordered (q|k|v, head, dim).
+ * y[m][n] = sum_k x[m][k] * w[n][k], bf16 in and out, fp32
  * accumulation, one rounding to nearest even at the end.  All three matrices are device memory,
  * row-major with row strides ldx, ldw, ldy in elements (multiples of 8, 16-byte aligned bases);
  * nothing is allocated and nothing but y[0..m_rows) x [0..n_out) is written.  The QKV projection
@@ -225,15 +226,6 @@ int32_t ca_set_kernel_variant(ca_ctx* ctx, int32_t variant);
  * otherwise); m_rows is free (0: nothing is done, CA_OK). */
 int32_t layer_linear_bf16(const void* x_dev, const void* w_dev, void* y_dev, int64_t m_rows, int32_t n_out,
                           int32_t k_in, int64_t ldx, int64_t ldw, int64_t ldy, void* hip_stream);
-
-/* Measurement aid, not a step of the method: runs v_mfma_f32_32x32x16_bf16 back to back on every
- * CU (nothing else in the loop) and reports the sustained dense bf16 rate and the shader clock the
- * chip held meanwhile -- the practical ceiling to read cascade_attn_forward's TFLOP/s against.
- * data_kind 0: all-zero operands, 1: pseudo-random bf16 operands (more switching, lower clock).
- * trips: loop trips of 32 MFMAs per wave (100000 runs ~15 ms).  scratch_dev: device memory, at
- * least 16 bytes per CU, overwritten.  Synchronises the stream.  Either output may be NULL. */
-int32_t ca_mfma_microbench(int32_t data_kind, int32_t trips, void* scratch_dev, size_t scratch_bytes,
-                           void* hip_stream, double* tflops, double* clock_ghz);
 
 /* ---- Cascade scheduler: the control flow of Algorithm 1, host integers only.
  * State (b, tau, d) = primary block, timestep index of the primary block, cascade depth.  An
@@ -269,7 +261,8 @@ int32_t ca_sched_state(const ca_sched* s, int64_t* b, int32_t* tau, int32_t* d, 
 
 const char* ca_strerror(int32_t code);
 
-/* Text of the HIP error behind the calling thread's most recent CA_EDEVICE ("" if none). */
+/* Text of the HIP error behind the calling thread's most recent CA_EDEVICE ("" if none): error
+ * reporting of this boundary, no counterpart in the paper. */
 const char* ca_last_device_error(void);
 
 #ifdef __cplusplus

@@ -4,6 +4,7 @@
 #include <new>
 
 #include "ca_internal.hpp"
+#include "cascade_attn_lab.h"
 
 namespace {
 

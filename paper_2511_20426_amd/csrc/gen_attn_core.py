@@ -54,15 +54,7 @@ import sys
 sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 from issue_sched import Atom, quanta, schedule  # noqa: E402
 
-# Timing experiments only (CA_ABL in the environment of the build): switch parts of the loop off.
-# 1 no softmax arithmetic, 2 no LDS operand reads, 4 no page loads, 8 no barriers.  Results are
-# then meaningless; the shipped library is always built with 0.
-ABL = int(os.environ.get("CA_ABL", "0"))
-
-# Schedule parameters can be overridden for tuning runs: CA_TUNE="cap=8.2,d_ahead=4,kbar=8,kr2=3,espread=24"
-TUNE = dict(kv.split("=") for kv in os.environ.get("CA_TUNE", "").split(",") if kv)
-
-D_AHEAD = int(TUNE.get("d_ahead", 5))          # operand fragments are read this many MFMA pairs ahead of use
+D_AHEAD = 5          # operand fragments are read this many MFMA pairs ahead of use
 PAGE = 32768
 VRING = 65536
 
@@ -193,11 +185,9 @@ def v_address_lines():
 def page_load_lines(i, lds_slot_off, which):
     """Load number i (0..7) of a page: 64 lanes x 16 B -> 1 KB of LDS at slot + 4096 i + 1024 wave
     (M0 carries the LDS address, the VGPR the byte offset in the page)."""
-    lines = [f"s_add_u32 m0, s{S_M0B}, {lds_slot_off + 4096 * i}"]
-    if not ABL & 4:
-        a = S_ADDRV if which else S_ADDR
-        lines.append(f"global_load_lds_dwordx4 {V(DMAOFF + i)}, s[{a}:{a + 1}]")
-    return lines
+    a = S_ADDRV if which else S_ADDR
+    return [f"s_add_u32 m0, s{S_M0B}, {lds_slot_off + 4096 * i}",
+            f"global_load_lds_dwordx4 {V(DMAOFF + i)}, s[{a}:{a + 1}]"]
 
 
 def emit_issue_page(E, which, lds_slot_off):
@@ -258,13 +248,13 @@ def p_word(p_base, j):
 
 # ---------------------------------------------------------------------------- issue-slot scheduling
 # (model and scheduler: issue_sched.py)
-CAP = float(TUNE.get("cap", 8.2))
+CAP = 8.2            # issue quanta per MFMA slot the scheduler may fill (8 = the slot; a little over pays)
 
 
-E_SPREAD = int(TUNE.get("espread", 22))    # the 32 exponentials of a step are due by this slot
+E_SPREAD = 22        # the 32 exponentials of a step are due by this slot
 THRESH = "0x47800000"     # 2^16: a step's row sum of 16 probabilities above this moves the reference
-K_BARRIER_SLOT = int(TUNE.get("kbar", 16))       # step 2: K(q+1) visible, slot of K(q) free
-N_KLOADS_R2 = int(TUNE.get("kr2", 2))           # of the 8 loads of K(q+2), how many issue in step 2 (the rest in step 3)
+K_BARRIER_SLOT = 16  # step 2: K(q+1) visible, slot of K(q) free
+N_KLOADS_R2 = 2      # of the 8 loads of K(q+2), how many issue in step 2 (the rest in step 3)
 
 
 def build_step(R, par):
@@ -283,55 +273,52 @@ def build_step(R, par):
         else:
             g = f - 8
             mfma[i] = mfma_pv(g & 3, nt, f, p_prev, g >> 2)
-        if nt == 0 and not ABL & 2:                        # operand prefetch, D_AHEAD pairs ahead
+        if nt == 0:                                        # operand prefetch, D_AHEAD pairs ahead
             fa = f + D_AHEAD
             src = frag_source(R, par, fa) if fa < 16 else frag_source(nR, npar, fa - 16)
             head[i].append(ds_read_frag(fa % 16, src))
         # what must precede the next MFMA: every other pair waits for its two fragments
-        if (i + 1) % 4 == 0 and not ABL & 2:
+        if (i + 1) % 4 == 0:
             tail[i].append(f"s_waitcnt lgkmcnt({D_AHEAD - 2})")
     if R == 0:                                             # before step 1: V(q) visible, V(q-1)'s slot free
-        tail[31] += ["s_waitcnt vmcnt(@VMCNT_V@)"] + ([] if ABL & 8 else ["s_barrier"])
+        tail[31] += ["s_waitcnt vmcnt(@VMCNT_V@)", "s_barrier"]
     if R == 2:
-        tail[K_BARRIER_SLOT - 1] += ["s_waitcnt vmcnt(@VMCNT_K@)"] + ([] if ABL & 8 else ["s_barrier"])
+        tail[K_BARRIER_SLOT - 1] += ["s_waitcnt vmcnt(@VMCNT_K@)", "s_barrier"]
 
     atoms = []
-    if not ABL & 1:
-        # row sums of the previous step join the running sums; this step's start afresh
-        lacc = [Atom([f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(TS[nt])}"], 0, 0, hard=1) for nt in range(2)]
-        atoms += lacc
-        exps = [Atom([f"v_exp_f32 {V(PX + e)}, {V(s_cur + e)}"], 0, (e * E_SPREAD) // 32, hard=min(E_SPREAD + 4, 27)) for e in range(32)]
-        atoms += exps
-        last_sum = [None, None]
-        for j in range(1, 32, 2):
-            nt = j >> 4
-            deps, dl = [exps[j - 1], exps[j]], (j * E_SPREAD) // 32 + 5
-            atoms.append(Atom([f"v_cvt_pk_bf16_f32 {V(p_word(p_cur, j))}, {V(PX + j - 1)}, {V(PX + j)}"],
-                              0, dl, deps, 2, hard=29))
-            if last_sum[nt] is None:
-                sm = [Atom([f"v_add_f32 {V(TS[nt])}, {V(PX + j - 1)}, {V(PX + j)}"], 0, dl, deps, 2, hard=28)]
-                sm[0].after.append((lacc[nt], 0))
-            else:
-                sm = [Atom([f"v_add_f32 {V(TS[nt])}, {V(TS[nt])}, {V(PX + k)}"], 0, dl, deps, 2, hard=28)
-                      for k in (j - 1, j)]
-                sm[0].after.append((last_sum[nt], 0))
-                sm[1].after.append((sm[0], 0))
-            atoms += sm
-            last_sum[nt] = sm[-1]
-        # is the tile just produced the ragged tail of a block's last page?
-        pg, sub = (S_PGCUR, R + 1) if R < 3 else (S_PGNEXT, 0)
-        rag = Atom([f"s_cmp_eq_u32 s{pg}, s{S_PM1}",
-                    f"s_cselect_b64 s[{S_RG}:{S_RG + 1}], s[{S_VLP + 2 * sub}:{S_VLP + 2 * sub + 1}], 0"], 0, 6, hard=24)
-        det = Atom([f"v_max_f32 {V(RT[1])}, {V(TS[0])}, {V(TS[1])}",
-                    f"v_cmp_lt_f32 vcc, {THRESH}, {V(RT[1])}"], 0, 28, [last_sum[0], last_sum[1]], 0, hard=29)
-        # scc travels from here to the branch after the last MFMA: nothing that writes scc may
-        # issue in slots 30 and 31 (every such atom has hard <= 29)
-        orr = Atom([f"s_or_b64 s[{S_T + 8}:{S_T + 9}], vcc, s[{S_RG}:{S_RG + 1}]"], 30, 30, [det, rag], 1, hard=30)
-        atoms += [rag, det, orr]
-        tail[31].insert(0, f"{back}:")
-        tail[31].insert(0, f"s_cbranch_scc1 {cold}")
-    else:
-        rag = None
+    # row sums of the previous step join the running sums; this step's start afresh
+    lacc = [Atom([f"v_add_f32 {V(LACC + 2 * nt)}, {V(LACC + 2 * nt)}, {V(TS[nt])}"], 0, 0, hard=1) for nt in range(2)]
+    atoms += lacc
+    exps = [Atom([f"v_exp_f32 {V(PX + e)}, {V(s_cur + e)}"], 0, (e * E_SPREAD) // 32, hard=min(E_SPREAD + 4, 27)) for e in range(32)]
+    atoms += exps
+    last_sum = [None, None]
+    for j in range(1, 32, 2):
+        nt = j >> 4
+        deps, dl = [exps[j - 1], exps[j]], (j * E_SPREAD) // 32 + 5
+        atoms.append(Atom([f"v_cvt_pk_bf16_f32 {V(p_word(p_cur, j))}, {V(PX + j - 1)}, {V(PX + j)}"],
+                          0, dl, deps, 2, hard=29))
+        if last_sum[nt] is None:
+            sm = [Atom([f"v_add_f32 {V(TS[nt])}, {V(PX + j - 1)}, {V(PX + j)}"], 0, dl, deps, 2, hard=28)]
+            sm[0].after.append((lacc[nt], 0))
+        else:
+            sm = [Atom([f"v_add_f32 {V(TS[nt])}, {V(TS[nt])}, {V(PX + k)}"], 0, dl, deps, 2, hard=28)
+                  for k in (j - 1, j)]
+            sm[0].after.append((last_sum[nt], 0))
+            sm[1].after.append((sm[0], 0))
+        atoms += sm
+        last_sum[nt] = sm[-1]
+    # is the tile just produced the ragged tail of a block's last page?
+    pg, sub = (S_PGCUR, R + 1) if R < 3 else (S_PGNEXT, 0)
+    rag = Atom([f"s_cmp_eq_u32 s{pg}, s{S_PM1}",
+                f"s_cselect_b64 s[{S_RG}:{S_RG + 1}], s[{S_VLP + 2 * sub}:{S_VLP + 2 * sub + 1}], 0"], 0, 6, hard=24)
+    det = Atom([f"v_max_f32 {V(RT[1])}, {V(TS[0])}, {V(TS[1])}",
+                f"v_cmp_lt_f32 vcc, {THRESH}, {V(RT[1])}"], 0, 28, [last_sum[0], last_sum[1]], 0, hard=29)
+    # scc travels from here to the branch after the last MFMA: nothing that writes scc may
+    # issue in slots 30 and 31 (every such atom has hard <= 29)
+    orr = Atom([f"s_or_b64 s[{S_T + 8}:{S_T + 9}], vcc, s[{S_RG}:{S_RG + 1}]"], 30, 30, [det, rag], 1, hard=30)
+    atoms += [rag, det, orr]
+    tail[31].insert(0, f"{back}:")
+    tail[31].insert(0, f"s_cbranch_scc1 {cold}")
     # page traffic
     loads = []
     if R == 0:                                             # address of V(q+1), then of K(q+2)
@@ -353,7 +340,7 @@ def build_step(R, par):
         # page-in-block counters of pages q and q+1 move on; one page less to go
         pe = Atom([f"s_mov_b32 s{S_PGCUR}, s{S_PGNEXT}", f"s_add_u32 s{S_T}, s{S_PGNEXT}, 1",
                    f"s_cmp_eq_u32 s{S_T}, s{S_P}", f"s_cselect_b32 s{S_PGNEXT}, 0, s{S_T}",
-                   f"s_sub_u32 s{S_NLEFT}, s{S_NLEFT}, 1"], 0, 20, [rag] if rag else [], 1, hard=29)
+                   f"s_sub_u32 s{S_NLEFT}, s{S_NLEFT}, 1"], 0, 20, [rag], 1, hard=29)
         atoms.append(pe)
     atoms += loads
 
@@ -438,8 +425,7 @@ def emit_step(E, R, par, vmcnt):
         E.e(m)
         for ln in lines:
             E.e(ln.replace("@VMCNT_V@", str(vmcnt[0])).replace("@VMCNT_K@", str(vmcnt[1])))
-    if not ABL & 1:
-        emit_cold(E, *cold_args)
+    emit_cold(E, *cold_args)
 
 
 def wait_counts():

@@ -43,12 +43,7 @@ import sys
 sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 from issue_sched import Atom, quanta, schedule  # noqa: E402
 
-# Timing experiments only (CA_GEMM_ABL in the environment of the build): 2 no LDS operand reads,
-# 4 no global loads, 8 no barriers.  Results are then meaningless; the shipped
-# library uses 0.
-ABL = int(os.environ.get("CA_GEMM_ABL", "0"))
-TUNE = dict(kv.split("=") for kv in os.environ.get("CA_GEMM_TUNE", "").split(",") if kv)
-CAP = float(TUNE.get("cap", 4.2))   # issue quanta between two MFMAs of 16 cycles
+CAP = 4.2                # issue quanta between two MFMAs of 16 cycles
 PART = 32768             # bytes of one operand's rows of one stage
 NW, NX = 3, 2            # ring depths; LDS = [W ring][X ring] = 160 KB
 XBASE = NW * PART
@@ -81,8 +76,6 @@ def mfma(b, ti, tj):
 
 
 def read_frag(b, op, t, stage, kk):
-    if ABL & 2:
-        return "s_nop 0"
     addr = (ADDRW + 2 * (stage % NW) if op == 0 else ADDRX + 2 * (stage % NX)) + kk
     return f"ds_read_b128 {V(frag(b, op, t), 4)}, {V(addr)} offset:{2048 * t}"
 
@@ -92,10 +85,8 @@ def load_lines(op, stage, i):
     -> 1 KB of LDS."""
     ring = (stage % NW) * PART if op == 0 else XBASE + (stage % NX) * PART
     base, off = (S_BW, OFFW) if op == 0 else (S_BX, OFFX)
-    lines = [f"s_add_u32 m0, s{S_M0B}, {ring + 1024 * i}"]
-    if not ABL & 4:
-        lines.append(f"global_load_lds_dwordx4 {V(off + i)}, s[{base}:{base + 1}]")
-    return lines
+    return [f"s_add_u32 m0, s{S_M0B}, {ring + 1024 * i}",
+            f"global_load_lds_dwordx4 {V(off + i)}, s[{base}:{base + 1}]"]
 
 
 def advance_lines(base, counter):
@@ -107,7 +98,7 @@ def advance_lines(base, counter):
 
 # fragments in the order the MFMAs (ti outer, tj inner) first need them
 READ_ORDER = [(0, 0)] + [(1, t) for t in range(8)] + [(0, t) for t in range(1, 8)]
-X_BY = int(TUNE.get("xby", 40))    # the 8 X loads of a stage issue within this many slots behind the barrier
+X_BY = 40               # the 8 X loads of a stage issue within this many slots behind the barrier
 
 
 def build_stage(P):
@@ -120,7 +111,7 @@ def build_stage(P):
                 mf.append(mfma(kk, ti, tj))
     # before the last k-step: this stage's last fragments are in registers; everything but the
     # W loads issued last has landed; behind the barrier this stage's buffers are free
-    tail[half - 1] += ["s_waitcnt vmcnt(@VM@) lgkmcnt(0)"] + ([] if ABL & 8 else ["s_barrier"])
+    tail[half - 1] += ["s_waitcnt vmcnt(@VM@) lgkmcnt(0)", "s_barrier"]
     tail[SLOTS - 1] += ["s_waitcnt lgkmcnt(0)"]
     atoms = []
     for kk in range(2):

@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "ca_internal.hpp"
+#include "cascade_attn_lab.h"
 
 namespace ca {
 
