@@ -73,6 +73,55 @@ def cpu_baseline(w, seconds_target=15.0):
     }
 
 
+def time_attention_only(torch, W, B, w, modes, shares=(), launches=5, pool=None):
+    """Attention launches of workload `w` on a steady-state pool (n_cached clean blocks, the
+    in-flight ones appended, Q rotated), timed with events around `launches` forwards after two
+    warm-up calls.  Returns {label: {"ms", "TFLOP/s", "frac"}}; `shares`: also one device's share
+    (queries of in-flight block i only) per mode."""
+    from paper_2511_20426_amd.runner import CascadePool
+    dev = torch.device("cuda:0")
+    L, H, D, C = w.block_tokens, w.heads, w.head_dim, w.n_inflight
+    own = pool is None
+    if own:
+        pool = CascadePool.for_workload(w, device=dev)
+        gen = torch.Generator(device=dev).manual_seed(w.seed + 1)
+        draw = lambda n: (torch.randn((n, H, D), generator=gen, device=dev) * w.input_scale).to(torch.bfloat16)
+        kb, vb = [draw(L) for _ in range(C)], [draw(L) for _ in range(C)]
+        for g in range(w.n_cached):
+            pool.append(g, 0, 0, kb[g % C], vb[g % C])
+            pool.ctx.kv_cache_promote(g)
+        infl = list(range(w.n_cached, w.n_cached + C))
+        pool.append_batch(infl, list(W.TIMESTEPS[::-1][:C]), 0, kb, vb)
+        q_rot = pool.rope(draw(C * L), w.frames_per_block * infl[0])
+    else:
+        pool, infl, q_rot = pool
+    out = torch.empty_like(q_rot)
+    res = {}
+    cases = [(m, None) for m in modes] + [(m, s) for m in modes for s in shares]
+    for mode, share in cases:
+        def run():
+            if share is None:
+                pool.forward(q_rot, infl, mode, out=out)
+            else:
+                pool.forward(q_rot[:L], infl, mode, out=out[:L], share=(share, 1))
+        run(); run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(launches):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / launches
+        causal = mode == B.CA_BLOCK_CAUSAL
+        if share is None:
+            flops = w.flops(block_causal=causal)
+        else:
+            flops = 4.0 * D * L * (w.n_cached + (share + 1 if causal else C)) * L * H
+        label = ("block_causal" if causal else "bidirectional") + ("" if share is None else f", share of block {share}")
+        res[label] = {"ms": ms, "TFLOP/s": flops / ms / 1e9, "frac": flops / ms / 1e9 / PEAK_BF16_TFLOPS}
+    return res
+
+
 # The projections either side of the attention at the Wan-14B width for five blocks in flight
 # (not part of the default step: --workload linear_qkv_14b / linear_out_14b)
 LINEAR_WORKLOADS = {"linear_qkv_14b": (23400, 15360, 5120), "linear_out_14b": (23400, 5120, 5120)}
@@ -148,6 +197,8 @@ def main() -> int:
                          "in-flight block SHARE (0 = oldest) are rotated and attended; the five appends stand "
                          "in for the K/V exchange")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the attention-only timings of the other shapes and modes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 1 GiB device copy instead (known traffic, for scaling rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -279,7 +330,9 @@ def main() -> int:
                      "avg_launch_ms": attn_ms,
                      "traffic": ATTN_TRAFFIC_BYTES_C4 if (w.name == "c4_wan14b_cascade5" and
                                                           mode == B.CA_BIDIRECTIONAL and
-                                                          args.share is None) else None},
+                                                          args.share is None) else None,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this "
+                                       "command (profiles/c4_wan14b_cascade5_hbm_traffic.txt), not measured in this run"},
     }
     # the two HBM-bound steps: every element read once and written once
     eb = 2 if w.dtype == "bf16" else 4
@@ -300,6 +353,33 @@ def main() -> int:
         "random_operands": {"TFLOP/s": rnd[0], "clock_GHz": rnd[1]},
         "zero_operands": {"TFLOP/s": zer[0], "clock_GHz": zer[1]},
         "achieved_over_random_operands": achieved / rnd[0]}
+    # The other shapes and modes of the method, attention launch alone (events, a few launches
+    # each): the headline workload in block-causal mode (Sec. 4.2) and as one device's share under
+    # the paper's temporal parallelism (Sec. 3.3), the Wan-1.3B cascade in both modes, and the
+    # sequential one-block baseline (cascade type P1 of Fig. 7).
+    if (w.name == "c4_wan14b_cascade5" and mode == B.CA_BIDIRECTIONAL and args.share is None
+            and not args.no_secondary):
+        both = (B.CA_BIDIRECTIONAL, B.CA_BLOCK_CAUSAL)
+        infl = list(range(state["b"], state["b"] + C))              # the next iteration's blocks, published
+        pool.append_batch(infl, timesteps[:C], 0, k_blocks, v_blocks)
+        pool.rope(q, w.frames_per_block * infl[0], out=q_rot)
+        result["secondary"]["attention_only"] = {
+            "c4_wan14b_cascade5": time_attention_only(torch, W, B, w, both, shares=(0, C - 1), pool=(pool, infl, q_rot)),
+            "c3_wan1p3b_cascade5": time_attention_only(torch, W, B, W.CONFIGS["c3_wan1p3b_cascade5"], both),
+            "c2_wan1p3b_seq": time_attention_only(torch, W, B, W.CONFIGS["c2_wan1p3b_seq"], (B.CA_BIDIRECTIONAL,)),
+        }
+        # cascade types P1..P4 (Fig. 7: 1, 2, 3, 5 blocks in flight) at the 14B shape, on the 6-block
+        # clean window of the headline and on the paper's own window accounting (7 blocks = 5 in
+        # flight + 2 cached, Sec. 4)
+        from dataclasses import replace
+        sweep = {}
+        for nc in (6, 2):
+            for ni in (1, 2, 3, 5):
+                if (ni, nc) == (w.n_inflight, w.n_cached):
+                    continue                                            # the headline itself
+                wv = replace(w, name=f"{w.name}[inflight={ni},cached={nc}]", n_inflight=ni, n_cached=nc)
+                sweep[f"inflight={ni},cached={nc}"] = time_attention_only(torch, W, B, wv, (B.CA_BIDIRECTIONAL,))["bidirectional"]
+        result["secondary"]["attention_only"]["cascade_types_14b"] = sweep
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result))
