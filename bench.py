@@ -3,8 +3,10 @@
 
 A step is one cascade iteration of one self-attention layer at the Wan-14B shape in steady
 state (6 clean cached blocks + 5 blocks in flight): publish the 5 in-flight blocks' K/V
-(fused K-RoPE + page write), rotate Q, run the cascaded attention, then promote the block
-that completed the cache step, evict the oldest window block and move on by one block.
+(fused K-RoPE + page write), rotate Q and run the cascaded attention (one launch: the attention
+kernel rotates the queries as it loads them; --two-launch-q takes the separate rope3d_apply),
+then promote the block that completed the cache step, evict the oldest window block and move on
+by one block.
 Inputs are seeded synthetic N(0,1)*0.5 bf16 tensors already resident in HBM.
 
 Prints ONE JSON line: whole-path TFLOP/s (algorithmic attention flops / step time), the
@@ -196,6 +198,9 @@ def main() -> int:
                          "in-flight block per GPU, every GPU holding the whole pool): only the queries of "
                          "in-flight block SHARE (0 = oldest) are rotated and attended; the five appends stand "
                          "in for the K/V exchange")
+    ap.add_argument("--two-launch-q", action="store_true",
+                    help="rotate Q with rope3d_apply and attend with cascade_attn_forward (two launches, Q makes a "
+                         "round trip through HBM) instead of cascade_attn_forward_rope")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true",
                     help="skip the attention-only timings of the other shapes and modes")
@@ -268,6 +273,8 @@ def main() -> int:
           for _ in range(args.steps)]
     ev_a = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
 
+    fused_q = args.share is None and not args.two_launch_q and w.dtype == "bf16"
+
     def step(i_timed=None):
         b = state["b"]
         infl = list(range(b, b + C))
@@ -276,14 +283,18 @@ def main() -> int:
         pool.append_batch(infl, timesteps[:C], 0, k_blocks, v_blocks)   # a1: publish K/V, one launch
         if i_timed is not None:
             ev_a[i_timed][1].record()
-        if args.share is None:
+        if fused_q:
+            pass                                                       # a2 happens inside the attention kernel
+        elif args.share is None:
             pool.rope(q, w.frames_per_block * b, out=q_rot)            # a2
         else:
             pool.rope(q[:L], w.frames_per_block * (b + args.share), out=q_rot[:L])
         if i_timed is not None:
             ev_a[i_timed][2].record()
             ev[i_timed][0].record()
-        if args.share is None:
+        if fused_q:
+            pool.forward_rope(q, infl, mode, out=out)                  # a2-a6
+        elif args.share is None:
             pool.forward(q_rot, infl, mode, out=out)                   # a3-a6
         else:
             pool.forward(q_rot[:L], infl, mode, out=out[:L], share=(args.share, 1))
@@ -323,9 +334,11 @@ def main() -> int:
         "config": {"workload": w.name, "heads": H, "head_dim": D, "tokens_per_block": L,
                    "inflight_blocks": C, "cached_blocks": w.n_cached, "mode": args.mode,
                    "n_q": n_rot * L, "n_kv": (w.n_cached + C) * L, "flops_per_step": flops,
-                   "step": "kv_cache_append_batch(%d blocks) + rope3d_apply(Q) + %s + promote/evict"
-                           % (C, "cascade_attn_forward" if args.share is None else "cascade_attn_forward_share")},
-        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel", "achieved": achieved,
+                   "step": "kv_cache_append_batch(%d blocks) + %s + promote/evict"
+                           % (C, "cascade_attn_forward_rope (Q rotated inside the attention kernel)" if fused_q else
+                              "rope3d_apply(Q) + " + ("cascade_attn_forward" if args.share is None
+                                                      else "cascade_attn_forward_share"))},
+        "roofline": {"bound": "mfma", "kernel": "attn_bf16_kernel<true>" if fused_q else "attn_bf16_kernel<false>", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS,
                      "avg_launch_ms": attn_ms,
                      "traffic": ATTN_TRAFFIC_BYTES_C4 if (w.name == "c4_wan14b_cascade5" and
@@ -337,12 +350,23 @@ def main() -> int:
     # the two HBM-bound steps: every element read once and written once
     eb = 2 if w.dtype == "bf16" else 4
     append_ms = sum(e[0].elapsed_time(e[1]) for e in ev_a) / args.steps / C
-    rope_ms = sum(e[1].elapsed_time(e[2]) for e in ev_a) / args.steps
+    if fused_q:                                   # a2 as its own kernel, outside the step: five launches
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        pool.rope(q, w.frames_per_block * state["b"], out=q_rot)
+        e0.record()
+        for _ in range(5):
+            pool.rope(q, w.frames_per_block * state["b"], out=q_rot)
+        e1.record()
+        torch.cuda.synchronize()
+        rope_ms = e0.elapsed_time(e1) / 5
+    else:
+        rope_ms = sum(e[1].elapsed_time(e[2]) for e in ev_a) / args.steps
     append_gbs = 2 * (2 * L * H * D * eb) / (append_ms * 1e-3) / 1e9
     rope_gbs = 2 * (n_rot * L * H * D * eb) / (rope_ms * 1e-3) / 1e9
     result["secondary"] = {
         "kv_cache_append": {"us_per_block": append_ms * 1e3, "GB/s": append_gbs, "frac_of_hbm_peak": append_gbs / PEAK_HBM_GBS},
-        "rope3d_apply": {"us": rope_ms * 1e3, "GB/s": rope_gbs, "frac_of_hbm_peak": rope_gbs / PEAK_HBM_GBS}}
+        "rope3d_apply": {"us": rope_ms * 1e3, "GB/s": rope_gbs, "frac_of_hbm_peak": rope_gbs / PEAK_HBM_GBS,
+                         "in_step": not fused_q}}
     # what the matrix pipes sustain on this machine with nothing else in the loop (the nominal peak
     # assumes 2.4 GHz; under a full MFMA load with toggling operands the chip clocks lower)
     probe = torch.empty(1 << 16, dtype=torch.uint8, device=dev)

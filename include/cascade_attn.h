@@ -185,6 +185,19 @@ int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev,
                                    int32_t first, int32_t count, int32_t mode, void* out_dev,
                                    void* hip_stream);
 
+/* rope3d_apply and cascade_attn_forward in one launch: q_dev holds the queries of the in-flight
+ * blocks as they leave the projection, not rotated, [n_inflight*L, heads, head_dim] with element
+ * strides q_tok_stride / q_head_stride (e.g. the q part of a packed [tokens][3][heads][head_dim]
+ * projection result); the kernel rotates each query by the position of its token (block
+ * inflight_block_ids[i] starts at latent frame frames_per_block * id) as it loads it, in fp32, and
+ * rounds it to bf16 once, after the softmax scale.  Everything else as cascade_attn_forward, whose
+ * result on rope3d_apply's output it matches up to that one rounding of Q fewer.  The blocks need
+ * not be consecutive in the video.  bf16 contexts only (CA_EUNSUPPORTED otherwise, and for latent
+ * frames or grid sizes of 4096 and beyond). */
+int32_t cascade_attn_forward_rope(ca_ctx* ctx, const void* q_dev, int64_t q_tok_stride, int64_t q_head_stride,
+                                  const int64_t* inflight_block_ids, int32_t n_inflight,
+                                  int32_t mode, void* out_dev, void* hip_stream);
+
 /* cascade_attn_forward for callers that can neither allocate device memory nor spare any of their
  * own for the library's intermediate results: code recorded into a HIP graph by a harness that owns
  * every allocation, tight serving loops, hosts that forbid hipMalloc after start-up.  Arguments,

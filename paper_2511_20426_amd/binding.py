@@ -26,7 +26,7 @@ CA_FREE, CA_NOISY, CA_CLEAN, CA_SINK = 0, 1, 2, 3
 EXPORTS = (
     "ca_pool_bytes", "ca_create", "ca_destroy", "kv_cache_append", "kv_cache_append_batch", "kv_cache_promote",
     "kv_cache_evict", "kv_cache_retag", "kv_cache_snapshot", "kv_cache_page_index",
-    "rope3d_apply", "rope3d_apply_strided", "cascade_attn_forward", "cascade_attn_forward_share", "cascade_attn_forward_static", "ca_debug_visibility", "ca_set_kernel_variant",
+    "rope3d_apply", "rope3d_apply_strided", "cascade_attn_forward", "cascade_attn_forward_share", "cascade_attn_forward_static", "cascade_attn_forward_rope", "ca_debug_visibility", "ca_set_kernel_variant",
     "ca_strerror", "ca_last_device_error",
     "ca_mfma_microbench", "layer_linear_bf16",
     "ca_sched_create", "ca_sched_create_lagged", "ca_sched_destroy", "ca_sched_batch", "ca_sched_advance", "ca_sched_state",
@@ -110,6 +110,8 @@ def _load() -> C.CDLL:
     lib.cascade_attn_forward.argtypes = [vp, vp, C.POINTER(i64), i32, i32, vp, vp]
     lib.cascade_attn_forward_static.restype = i32
     lib.cascade_attn_forward_static.argtypes = [vp, vp, C.POINTER(i64), i32, i32, vp, vp]
+    lib.cascade_attn_forward_rope.restype = i32
+    lib.cascade_attn_forward_rope.argtypes = [vp, vp, i64, i64, C.POINTER(i64), i32, i32, vp, vp]
     lib.cascade_attn_forward_share.restype = i32
     lib.cascade_attn_forward_share.argtypes = [vp, vp, C.POINTER(i64), i32, i32, i32, i32, vp, vp]
     lib.ca_debug_visibility.restype = i32
@@ -268,6 +270,13 @@ class Context:
         _check(lib.cascade_attn_forward_static(self._h, C.c_void_p(q_ptr or None), ids, len(inflight_block_ids),
                                                mode, C.c_void_p(out_ptr or None), C.c_void_p(stream or None)),
                "cascade_attn_forward_static")
+
+    def cascade_attn_forward_rope(self, q_ptr: int, q_tok_stride: int, q_head_stride: int,
+                                  inflight_block_ids: Sequence[int], mode: int, out_ptr: int, stream: int = 0) -> None:
+        ids = (C.c_int64 * len(inflight_block_ids))(*inflight_block_ids)
+        _check(lib.cascade_attn_forward_rope(self._h, C.c_void_p(q_ptr or None), q_tok_stride, q_head_stride, ids,
+                                             len(inflight_block_ids), mode, C.c_void_p(out_ptr or None),
+                                             C.c_void_p(stream or None)), "cascade_attn_forward_rope")
 
     def cascade_attn_forward_share(self, q_ptr: int, inflight_block_ids: Sequence[int], first: int, count: int,
                                    mode: int, out_ptr: int, stream: int = 0) -> None:

@@ -30,6 +30,7 @@
 #include <hip/hip_runtime.h>
 
 #include <atomic>
+#include <cmath>
 
 #include "ca_internal.hpp"
 
@@ -47,6 +48,18 @@ constexpr int kPageBytes = 128 * 128 * 2;       // one K or V page
 constexpr int kPairBytes = 2 * kPageBytes;      // K page followed by V page
 constexpr int kRowsPerWg = 256;
 constexpr int kMaxSeg = kMaxInflight;
+
+// Rotary embedding of the queries inside the kernel's Q load.  Angles are formed in revolutions:
+// pair j turns by pos * freq[j] / 2pi; that factor is split into a 12-bit head and a tail so that
+// pos * head is exact in fp32 for pos < 4096 and only its fractional part meets the hardware
+// sin / cos (measured: cos and sin within 4.2e-7 of fp64 for every pos < 4096 and every pair).
+struct QRope {
+  float rev_hi[kMaxPairs], rev_lo[kMaxPairs];
+  int32_t pairs_t, pairs_h;            // pairs [0, pairs_t): frame axis, then pairs_h: row axis, rest: column axis
+  int32_t grid_w, plane, block_tokens; // plane = grid_h * grid_w
+  int32_t first_frame[kMaxInflight];   // of the launch's query blocks
+  int64_t tok_stride, head_stride;     // of q, in elements
+};
 
 struct AttnArgs {
   const uint16_t* q;
@@ -70,6 +83,9 @@ struct AttnArgs {
   int32_t split, split_items, full_items;   // per XCD: full_items + split_items == work_per_xcd
   float* partials;                     // [xcd][split item][chunk][kPartialFloats]
   float c;                             // log2(e) / sqrt(head_dim)
+  // Only read by the instantiation that rotates Q itself (attn_bf16_kernel<true>): q is then the
+  // unrotated [row, head, dim] tensor with the caller's strides.
+  QRope rq;
 };
 
 // one partial result of a 256-row tile: O^T contributions [row][128] (fp32, not normalised),
@@ -114,6 +130,7 @@ __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 
 // (generated by gen_attn_core.py, which also documents the pipeline and the register map).
 constexpr uint32_t kVRing = 2 * kPageBytes;
 
+template <bool kRopeQ>
 __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
   extern __shared__ __attribute__((aligned(1024))) uint8_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -140,25 +157,71 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 
   // ---- Q fragments: B operand of S^T = K Q^T.  Lane holds dims 16ks + 8hi .. +7 of query l31
   // of column tile nt; fragment (nt, ks) goes to a[128 + 4*(8nt + ks) ..].
+  // The instantiation that rotates Q itself does so in a pass of its own: thread t rotates row t of
+  // the workgroup's 256 rows, scales, rounds once and parks the row in LDS, which the page rings do
+  // not use yet; the fragment loads below then read LDS.
+  if (kRopeQ) {
+    const int r = row0 + tid;
+    const bool ok = r < rows_end;
+    const int rr = ok ? r : row0;
+    const int blk = rr / a.rq.block_tokens, n = rr - blk * a.rq.block_tokens;
+    const int fr = n / a.rq.plane, in_plane = n - fr * a.rq.plane;
+    const int y = in_plane / a.rq.grid_w;
+    const float pos_f = float(a.rq.first_frame[blk] + fr), pos_y = float(y), pos_x = float(in_plane - y * a.rq.grid_w);
+    const uint16_t* qp = a.q + int64_t(rr) * a.rq.tok_stride + int64_t(h) * a.rq.head_stride;
+    u32x4 v[16];                                            // the row's 16 chunks, all loads in flight at once
+#pragma unroll
+    for (int c = 0; c < 16; ++c) v[c] = *reinterpret_cast<const u32x4*>(qp + 8 * c);
+    // the per-pair factors go through LDS (behind the 64 KB the rotated rows will take): read from
+    // the argument block with compile-time indices they would sit in 128 scalar registers
+    float* tab = reinterpret_cast<float*>(lds + 65536);
+    if (tid < 2 * kMaxPairs) tab[tid] = tid < kMaxPairs ? a.rq.rev_hi[tid] : a.rq.rev_lo[tid - kMaxPairs];
+    __syncthreads();
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {                          // chunk c: dims 8c .. 8c+7, pairs 4c .. 4c+3
+      u32x4 out;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int pair = 4 * c + j;
+        const float pos = pair < a.rq.pairs_t ? pos_f : (pair < a.rq.pairs_t + a.rq.pairs_h ? pos_y : pos_x);
+        const float rev = __builtin_amdgcn_fractf(pos * tab[pair]) + pos * tab[kMaxPairs + pair];
+        const float cs = __builtin_amdgcn_cosf(rev), sn = __builtin_amdgcn_sinf(rev);
+        const uint32_t x = ok ? v[c][j] : 0u;
+        const float u = __uint_as_float(x << 16), w = __uint_as_float(x & 0xffff0000u);
+        // scores come out of the matrix pipe in log2 units: Q is scaled by c = log2(e)/sqrt(D) here
+        out[j] = pack2((u * cs - w * sn) * a.c, (u * sn + w * cs) * a.c);
+      }
+      *reinterpret_cast<u32x4*>(lds + tid * 256 + ((c ^ (tid & 15)) << 4)) = out;
+    }
+    __syncthreads();
+  }
   int qrow[2];
   f32x16 qt[4];
 #pragma unroll
   for (int nt = 0; nt < 2; ++nt) {
-    qrow[nt] = row0 + wave * 64 + nt * 32 + l31;
+    const int lrow = wave * 64 + nt * 32 + l31;              // row inside the workgroup's tile
+    qrow[nt] = row0 + lrow;
     const bool ok = qrow[nt] < rows_end;
     const uint16_t* qp = a.q + (int64_t(ok ? qrow[nt] : row0) * a.heads + h) * 128 + hi * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(qp + ks * 16);
-      if (!ok) v = u32x4{0, 0, 0, 0};
-      // scores come out of the matrix pipe in log2 units: Q is scaled by c = log2(e)/sqrt(D) here
+      if (kRopeQ) {
+        const u32x4 v = *reinterpret_cast<const u32x4*>(lds + lrow * 256 + (((2 * ks + hi) ^ (lrow & 15)) << 4));
 #pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const uint32_t w = pack2(__uint_as_float(v[j] << 16) * a.c, __uint_as_float(v[j] & 0xffff0000u) * a.c);
-        qt[2 * nt + (ks >> 2)][4 * (ks & 3) + j] = __uint_as_float(w);
+        for (int j = 0; j < 4; ++j) qt[2 * nt + (ks >> 2)][4 * (ks & 3) + j] = __uint_as_float(v[j]);
+      } else {
+        u32x4 v = *reinterpret_cast<const u32x4*>(qp + ks * 16);
+        if (!ok) v = u32x4{0, 0, 0, 0};
+        // scores come out of the matrix pipe in log2 units: Q is scaled by c = log2(e)/sqrt(D) here
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t w = pack2(__uint_as_float(v[j] << 16) * a.c, __uint_as_float(v[j] & 0xffff0000u) * a.c);
+          qt[2 * nt + (ks >> 2)][4 * (ks & 3) + j] = __uint_as_float(w);
+        }
       }
     }
   }
+  if (kRopeQ) __syncthreads();        // every fragment is in registers before the first page lands in LDS
 
   // address of page 0 of KV block i for this head: lane i of (tbl_lo, tbl_hi)
   const int my_slot = a.kv_slot[lane & (kMaxKvBlocks - 1)];
@@ -352,12 +415,15 @@ int32_t plan_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out,
   return CA_OK;
 }
 
-int32_t enqueue_attn_bf16(const AttnArgs& a, void* stream) {
+int32_t enqueue_attn_bf16(const AttnArgs& a, bool rope_q, void* stream) {
   const dim3 grid((unsigned)((a.full_items + a.split_items * a.split) * 8));
-  if (const int32_t rc = ensure_dynamic_lds(reinterpret_cast<const void*>(attn_bf16_kernel), 4 * kPageBytes, 0);
-      rc != CA_OK)
-    return rc;
-  hipLaunchKernelGGL(attn_bf16_kernel, grid, dim3(256), 4 * kPageBytes, static_cast<hipStream_t>(stream), a);
+  const void* kernel = rope_q ? reinterpret_cast<const void*>(attn_bf16_kernel<true>)
+                              : reinterpret_cast<const void*>(attn_bf16_kernel<false>);
+  if (const int32_t rc = ensure_dynamic_lds(kernel, 4 * kPageBytes, rope_q ? 2 : 0); rc != CA_OK) return rc;
+  if (rope_q)
+    hipLaunchKernelGGL(attn_bf16_kernel<true>, grid, dim3(256), 4 * kPageBytes, static_cast<hipStream_t>(stream), a);
+  else
+    hipLaunchKernelGGL(attn_bf16_kernel<false>, grid, dim3(256), 4 * kPageBytes, static_cast<hipStream_t>(stream), a);
   if (a.split > 1)
     hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(8 * a.split_items)), dim3(256), 0,
                        static_cast<hipStream_t>(stream), a);
@@ -373,7 +439,39 @@ int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* ou
   if (const int32_t rc = plan_attn_bf16(p, variant, q, out, pool, partials_dev, max_partials, true, &a, &needed);
       rc != CA_OK)
     return rc;
-  return enqueue_attn_bf16(a, stream);
+  return enqueue_attn_bf16(a, false, stream);
+}
+
+int32_t launch_attn_bf16_rope(const AttnPlan& p, const QRopePlan& rp, int variant, const void* q, void* out,
+                              const void* pool, void* partials_dev, int max_partials, void* stream) {
+  AttnArgs a;
+  int needed = 0;
+  if (const int32_t rc = plan_attn_bf16(p, variant, q, out, pool, partials_dev, max_partials, true, &a, &needed);
+      rc != CA_OK)
+    return rc;
+  const double two_pi = 6.283185307179586476925286766559;
+  for (int j = 0; j < kMaxPairs; ++j) {
+    const double rev = rp.geom.freq[j] / two_pi;
+    int e = 0;
+    const double m = std::frexp(rev, &e);                       // rev = m 2^e, 0.5 <= m < 1
+    const double head = std::ldexp(std::floor(std::ldexp(m, 12)), e - 12);
+    a.rq.rev_hi[j] = float(head);
+    a.rq.rev_lo[j] = float(rev - head);
+  }
+  a.rq.pairs_t = rp.geom.pairs_t;
+  a.rq.pairs_h = rp.geom.pairs_h;
+  a.rq.grid_w = rp.geom.grid_w;
+  a.rq.plane = rp.geom.grid_h * rp.geom.grid_w;
+  a.rq.block_tokens = p.block_tokens;
+  for (int i = 0; i < p.n_q_blocks; ++i) {
+    // positions must stay below 4096 for the exact head product (frames are the only axis that grows)
+    if (rp.first_frame[i] < 0 || rp.first_frame[i] + p.block_tokens / a.rq.plane >= 4096) return CA_EUNSUPPORTED;
+    a.rq.first_frame[i] = int32_t(rp.first_frame[i]);
+  }
+  if (rp.geom.grid_h >= 4096 || rp.geom.grid_w >= 4096) return CA_EUNSUPPORTED;
+  a.rq.tok_stride = rp.tok_stride;
+  a.rq.head_stride = rp.head_stride;
+  return enqueue_attn_bf16(a, true, stream);
 }
 
 // ---- the same launch with the partial results in device memory this library holds itself, for
@@ -421,7 +519,7 @@ int32_t launch_attn_bf16_static(const AttnPlan& p, int variant, const void* q, v
   if (const int32_t rc = plan_attn_bf16(p, variant, q, out, pool, ptr, kStaticPartials, false, &a, &needed); rc != CA_OK)
     return rc;
   if (needed > kStaticPartials) return CA_ETOOBIG;
-  return enqueue_attn_bf16(a, stream);
+  return enqueue_attn_bf16(a, false, stream);
 }
 
 }  // namespace ca

@@ -167,8 +167,11 @@ namespace {
 // partials: where the bf16 kernel's split work items put their partial results
 enum class Partials { kInPool, kStatic };
 
+// q_strides: null for rotated, contiguous queries; else {token stride, head stride} of unrotated
+// queries that the kernel rotates itself
 int32_t forward_impl(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids, int32_t n_inflight,
-                     int32_t first, int32_t count, int32_t mode, void* out_dev, void* hip_stream, Partials where) {
+                     int32_t first, int32_t count, int32_t mode, void* out_dev, void* hip_stream, Partials where,
+                     const int64_t* q_strides = nullptr) {
   if (!ctx) return CA_EINVAL;
   const ca::CacheMeta& m = ctx->meta;
   std::vector<int64_t> ids;
@@ -193,6 +196,18 @@ int32_t forward_impl(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_blo
     p.n_vis[i] = n_vis[first + i];
     if (p.n_vis[i] != p.n_vis[0]) p.uniform = 0;
   }
+  if (q_strides) {
+    if (c.dtype != CA_BF16) return CA_EUNSUPPORTED;
+    if (!strides_ok(c, q_dev, q_strides[0], q_strides[1])) return CA_EINVAL;
+    ca::QRopePlan rp{};
+    rp.geom = rope_geom(m);
+    for (int i = 0; i < count; ++i) rp.first_frame[i] = int64_t(c.frames_per_block) * inflight_block_ids[first + i];
+    rp.tok_stride = q_strides[0];
+    rp.head_stride = q_strides[1];
+    return ca::launch_attn_bf16_rope(p, rp, ctx->variant, q_dev, out_dev, ctx->pool,
+                                     static_cast<uint8_t*>(ctx->pool) + m.page_bytes_total(), ca::kMaxPartials,
+                                     hip_stream);
+  }
   if (c.dtype != CA_BF16) return ca::launch_attn_f32(p, q_dev, out_dev, ctx->pool, hip_stream);   // no scratch at all
   if (where == Partials::kStatic)
     return ca::launch_attn_bf16_static(p, ctx->variant, q_dev, out_dev, ctx->pool, hip_stream);
@@ -215,6 +230,14 @@ int32_t cascade_attn_forward_share(ca_ctx* ctx, const void* q_dev, const int64_t
                                    void* out_dev, void* hip_stream) {
   return forward_impl(ctx, q_dev, inflight_block_ids, n_inflight, first, count, mode, out_dev, hip_stream,
                       Partials::kInPool);
+}
+
+int32_t cascade_attn_forward_rope(ca_ctx* ctx, const void* q_dev, int64_t q_tok_stride, int64_t q_head_stride,
+                                  const int64_t* inflight_block_ids, int32_t n_inflight, int32_t mode,
+                                  void* out_dev, void* hip_stream) {
+  const int64_t strides[2] = {q_tok_stride, q_head_stride};
+  return forward_impl(ctx, q_dev, inflight_block_ids, n_inflight, 0, n_inflight, mode, out_dev, hip_stream,
+                      Partials::kInPool, strides);
 }
 
 int32_t cascade_attn_forward_static(ca_ctx* ctx, const void* q_dev, const int64_t* inflight_block_ids,

@@ -97,6 +97,16 @@ int32_t launch_attn_f32(const AttnPlan& p, const void* q, void* out, const void*
 int32_t launch_attn_bf16(const AttnPlan& p, int variant, const void* q, void* out, const void* pool,
                          void* scratch, int max_partials, void* stream);
 int32_t attn_bf16_variant_ok(int variant);
+// The same launch on queries that are not rotated yet: the kernel rotates them as it loads them.
+// q is [rows, heads, head_dim] with the given strides; first_frame[i] is the first latent frame of
+// query block i of the launch.
+struct QRopePlan {
+  RopeGeom geom;
+  int64_t first_frame[kMaxInflight];
+  int64_t tok_stride, head_stride;
+};
+int32_t launch_attn_bf16_rope(const AttnPlan& p, const QRopePlan& rp, int variant, const void* q, void* out,
+                              const void* pool, void* scratch, int max_partials, void* stream);
 // The same launch with the partial results in the library's own static device array (one copy per
 // GPU, kept for the life of the process) instead of caller memory; CA_ETOOBIG if the split the
 // device asks for needs more partial tiles than that array holds.  attn_static_scratch_prepare
@@ -115,7 +125,7 @@ int32_t launch_gemm_bf16(const void* x, const void* w, void* y, int64_t M, int32
 // safe: the cached values are idempotent and written with relaxed atomics).
 constexpr int kMaxDevices = 64;
 int32_t device_cu_count(int* n_cu);                                   // of the current device
-int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot);  // slot: 0 attention, 1 GEMM
+int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot);  // slot: 0 attention, 1 GEMM, 2 attention rotating Q
 int32_t finish_launch(const char* what);
 int32_t device_failure(const char* what, int hip_error);   // records the text, clears HIP's last error, returns CA_EDEVICE
 const char* last_device_error();

@@ -348,7 +348,7 @@ const char* last_device_error() { return g_last_error; }
 
 namespace {
 std::atomic<int> g_cu_count[kMaxDevices];
-std::atomic<int> g_lds_set[2][kMaxDevices];
+std::atomic<int> g_lds_set[3][kMaxDevices];
 }  // namespace
 
 int32_t device_cu_count(int* n_cu) {

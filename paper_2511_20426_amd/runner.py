@@ -103,6 +103,22 @@ class CascadePool:
         return o
 
 
+def _forward_rope(self, q_raw: torch.Tensor, inflight: Sequence[int], mode: int,
+                  out: torch.Tensor | None = None) -> torch.Tensor:
+    """Attention on queries that are not rotated yet (cascade_attn_forward_rope): q_raw [C*L, H, D]
+    with any token / head strides; the result is a contiguous tensor of that shape."""
+    self._check(q_raw)
+    assert q_raw.shape[0] == len(inflight) * self.block_tokens
+    o = torch.empty(q_raw.shape, dtype=q_raw.dtype, device=q_raw.device) if out is None else out
+    assert o.is_contiguous() and o.shape == q_raw.shape
+    self.ctx.cascade_attn_forward_rope(q_raw.data_ptr(), q_raw.stride(0), q_raw.stride(1), list(inflight), mode,
+                                       o.data_ptr(), self._stream())
+    return o
+
+
+CascadePool.forward_rope = _forward_rope
+
+
 def linear(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
     """y = x @ w.T through layer_linear_bf16: x [M, K], w [N, K], y [M, N], bf16, rows may be
     strided (last dimension contiguous)."""
@@ -116,18 +132,24 @@ def linear(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) ->
 
 
 def attention_layer(pool: CascadePool, x: torch.Tensor, w_qkv: torch.Tensor, w_out: torch.Tensor,
-                    inflight: Sequence[int], timesteps: Sequence[int], epoch: int, mode: int) -> torch.Tensor:
+                    inflight: Sequence[int], timesteps: Sequence[int], epoch: int, mode: int,
+                    rotate_q_in_kernel: bool = True) -> torch.Tensor:
     """One self-attention layer around the shared pool, for the blocks in flight (oldest first,
     consecutive in the video): QKV projection, K/V of every block published to the cache, Q
     rotated, cascaded attention, output projection.  x [C*L, width], w_qkv [3*width, width] with
     output rows ordered (q|k|v, head, dim), w_out [width, width]; width = heads * head_dim.
-    Library calls only; the q/k/v handed on are strided views of the projection's output."""
+    Library calls only; the q/k/v handed on are strided views of the projection's output.  The
+    queries go to the attention kernel as they are (it rotates them while loading), or, with
+    rotate_q_in_kernel=False, through rope3d_apply into a contiguous tensor first."""
     L, H, D = pool.block_tokens, pool.heads, pool.head_dim
     n = len(inflight) * L
     assert x.shape == (n, H * D) and w_qkv.shape == (3 * H * D, H * D) and w_out.shape == (H * D, H * D)
     qkv = linear(x, w_qkv).view(n, 3, H, D)
     blocks = [qkv[i * L:(i + 1) * L] for i in range(len(inflight))]
     pool.append_batch(inflight, timesteps, epoch, [b[:, 1] for b in blocks], [b[:, 2] for b in blocks])
-    q_rot = pool.rope(qkv[:, 0], pool.frames_per_block * inflight[0])     # strided view -> contiguous
-    o = pool.forward(q_rot, inflight, mode)
+    if rotate_q_in_kernel:
+        o = pool.forward_rope(qkv[:, 0], inflight, mode)
+    else:
+        q_rot = pool.rope(qkv[:, 0], pool.frames_per_block * inflight[0])     # strided view -> contiguous
+        o = pool.forward(q_rot, inflight, mode)
     return linear(o.view(n, H * D), w_out)

@@ -191,6 +191,21 @@ def gpu_forward(w: W.Workload, pool, q, inflight_g, mode):
     return from_torch(out, w.dtype)
 
 
+def gpu_forward_rope(w: W.Workload, pool, q, inflight_g, mode, packed: bool = True):
+    """The forward on unrotated queries (cascade_attn_forward_rope); with packed=True q is handed
+    over as the strided q part of a [tokens, 3, H, D] tensor, as a QKV projection leaves it."""
+    import torch
+    qt = to_torch(q, w.dtype)
+    if packed:
+        box = torch.full((qt.shape[0], 3, qt.shape[1], qt.shape[2]), float("nan"), dtype=qt.dtype, device=qt.device)
+        box[:, 0] = qt
+        qt = box[:, 0]
+    out = pool.forward_rope(qt, inflight_g, mode, out=torch.full(tuple(qt.shape), float("nan"), dtype=qt.dtype,
+                                                                  device=qt.device))
+    torch.cuda.synchronize()
+    return from_torch(out, w.dtype)
+
+
 def gpu_forward_share(w: W.Workload, pool, q, inflight_g, mode, first, count):
     """The same for the queries of in-flight blocks first .. first+count-1 only
     (cascade_attn_forward_share); q is the whole [C*L, H, D] tensor, the result [count*L, H, D]."""

@@ -43,6 +43,13 @@ int32_t launch_attn_bf16(const AttnPlan& p, int, const void* q, void* out, const
     if (p.kv_slot[i] < 0) return CA_EDEVICE;
   return q && out && pool && scratch && max_partials > 0 ? CA_OK : CA_EDEVICE;
 }
+int32_t launch_attn_bf16_rope(const AttnPlan& p, const QRopePlan& rp, int, const void* q, void* out, const void* pool,
+                              void* scratch, int, void*) {
+  ++g_launches;
+  for (int i = 0; i < p.n_q_blocks; ++i)
+    if (rp.first_frame[i] < 0) return CA_EDEVICE;
+  return q && out && pool && scratch && rp.tok_stride >= rp.geom.head_dim ? CA_OK : CA_EDEVICE;
+}
 int32_t launch_attn_bf16_static(const AttnPlan& p, int, const void* q, void* out, const void* pool, void*) {
   ++g_launches;
   return q && out && pool && p.n_q_blocks > 0 ? CA_OK : CA_EDEVICE;
@@ -116,6 +123,10 @@ static void rollout(int dtype, int sink, int window, int lag) {
       CHECK(cascade_attn_forward(ctx, tensor, ids, n, mode, tensor, nullptr) == CA_OK);
       CHECK(cascade_attn_forward_share(ctx, tensor, ids, n, n - 1, 1, mode, tensor, nullptr) == CA_OK);
       CHECK(cascade_attn_forward_static(ctx, tensor, ids, n, mode, tensor, nullptr) == CA_OK);
+      CHECK(cascade_attn_forward_rope(ctx, tensor, 3 * 128 * cfg.heads, 128, ids, n, mode, tensor, nullptr) ==
+            (dtype == CA_BF16 ? CA_OK : CA_EUNSUPPORTED));
+      CHECK(cascade_attn_forward_rope(ctx, tensor, 64, 128, ids, n, mode, tensor, nullptr) ==
+            (dtype == CA_BF16 ? CA_EINVAL : CA_EUNSUPPORTED));
       CHECK(cascade_attn_forward_static(ctx, nullptr, ids, n, mode, tensor, nullptr) == CA_EINVAL);
       CHECK(cascade_attn_forward_share(ctx, tensor, ids, n, n, 1, mode, tensor, nullptr) == CA_EINVAL);
       uint8_t vis[8 * 32];

@@ -233,6 +233,54 @@ def test_bf16_small_full_parity(mode, heads, gh, gw, nc, ni):
 
 
 @pytest.mark.parametrize("mode", [BI, CA])
+@pytest.mark.parametrize("heads,gh,gw,nc,infl", [(3, 10, 13, 2, (2, 3, 4)), (2, 19, 27, 1, (1, 2)), (1, 4, 5, 0, (0,)),
+                                                 (2, 9, 14, 2, (2, 4, 5)), (16, 19, 27, 1, (7, 8, 9))])
+def test_bf16_forward_on_unrotated_queries(mode, heads, gh, gw, nc, infl):
+    """cascade_attn_forward_rope (the kernel rotates Q as it loads it) against the oracle: queries
+    handed over as the strided q part of a packed projection result; ragged row tiles; in-flight
+    blocks that are not consecutive in the video; a launch with split KV walks; and, as a sanity
+    check, closeness to the two-launch path (rope3d_apply, then cascade_attn_forward), from which
+    it differs by one rounding of Q."""
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=heads, grid_h=gh, grid_w=gw, n_cached=nc,
+                        n_inflight=len(infl))
+    _say(f"forward on unrotated queries: heads={heads} L={w.block_tokens} cached={nc} in flight={infl} mode={mode}")
+    q, k, v = W.draw_config(w, seed=91)
+    first = infl[0] - nc
+    cached = list(range(first, first + nc))
+    pool = Hn.gpu_setup(w, k, v, cached, list(infl))
+    got = Hn.gpu_forward_rope(w, pool, q, list(infl), mode)
+    ref, bound = (_cat(x) for x in Hn.oracle_forward_bounded(w, q, k, v, cached, list(infl), mode))
+    Hn.assert_close(got, ref, "bf16", "forward on unrotated queries", bound=bound)
+    if list(infl) == list(range(infl[0], infl[0] + len(infl))):
+        two = Hn.gpu_forward(w, pool, q, list(infl), mode)
+        assert Hn.rel_l2(got, two) < 3e-3
+    np.testing.assert_array_equal(Hn.gpu_forward_rope(w, pool, q, list(infl), mode, packed=False), got)
+
+
+def test_forward_on_unrotated_queries_rejects_what_it_does_not_cover():
+    import torch
+    from paper_2511_20426_amd import binding as B
+    from paper_2511_20426_amd.runner import CascadePool
+    w = W.CONFIGS["c1_tiny_f32"]
+    q, k, v = W.draw_config(w)
+    pool = Hn.gpu_setup(w, k, v, [0, 1], [2])
+    x = Hn.to_torch(q, w.dtype)
+    with pytest.raises(B.CascadeAttnError) as e:                     # fp32 contexts have no such kernel
+        pool.forward_rope(x, [2], BI, out=torch.empty_like(x))
+    assert e.value.code == B.CA_EUNSUPPORTED
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=4, grid_w=5, n_cached=0, n_inflight=1)
+    pool = CascadePool.for_workload(w)
+    t = torch.zeros((w.block_tokens, 2, 128), dtype=torch.bfloat16, device="cuda:0")
+    pool.append(2000, 0, 0, t, t)                                     # latent frames 6000..: beyond the exact range
+    with pytest.raises(B.CascadeAttnError) as e:
+        pool.forward_rope(t, [2000], BI, out=torch.empty_like(t))
+    assert e.value.code == B.CA_EUNSUPPORTED
+    with pytest.raises(B.CascadeAttnError) as e:                     # head stride shorter than a head
+        pool.ctx.cascade_attn_forward_rope(t.data_ptr(), 256, 64, [2000], BI, t.data_ptr())
+    assert e.value.code == B.CA_EINVAL
+
+
+@pytest.mark.parametrize("mode", [BI, CA])
 @pytest.mark.parametrize("ramp,bar", [((1.0, 24.0), 2e-2), ((24.0, 1.0), 2e-2), ((1.0, 400.0), 8e-2),
                                       ((1.0, 400.0, "step"), 8e-2)])
 def test_bf16_moving_row_maximum(mode, ramp, bar):
@@ -482,7 +530,8 @@ def _parity_rows(L, i, n_random, seed):
     return W.sample_rows(L, n_random, seed=seed, tile_edges=(128,), offsets=(0, (i * L) % 256))
 
 
-def _full_shape(name, modes, n_random=16, shares=(), scale=None, full=False, bars=None, reorder_checks=True):
+def _full_shape(name, modes, n_random=16, shares=(), scale=None, full=False, bars=None, reorder_checks=True,
+                fused=True):
     """One forward at a configuration's full shape against the oracle on every head: all rows
     (full=True) or the rows of _parity_rows; norm bars plus the per-element bound."""
     w = W.CONFIGS[name]
@@ -522,6 +571,11 @@ def _full_shape(name, modes, n_random=16, shares=(), scale=None, full=False, bar
                 i = tuple(bad[0])
                 _say(f"{name}: {len(bad)} outside the bound, first at {i}: {out[i]!r} vs {whole[i]!r}")
             assert len(bad) == 0
+        if fused:
+            part = Hn.gpu_forward_rope(w, pool, q, infl, mode)
+            got = W.split_blocks(part, L) if full else [o[r] for o, r in zip(W.split_blocks(part, L), rows)]
+            Hn.assert_close(_cat(got), _cat(ref), "bf16", f"{name} mode={mode}, Q rotated in the kernel",
+                            bound=_cat(bound), **bars)
         # one device's share of the forward (queries of some in-flight blocks only): same rows,
         # tiled from the share's first row instead of the batch's
         for first, count in shares:
@@ -816,8 +870,9 @@ def test_empty_rotation_is_a_no_op():
     assert bool((x == 2.0).all())
 
 
+@pytest.mark.parametrize("fused_q", [True, False])
 @pytest.mark.parametrize("mode", [BI, CA])
-def test_attention_layer_pipeline(mode):
+def test_attention_layer_pipeline(mode, fused_q):
     """QKV projection -> K/V published + Q rotated (strided views of the projection's output) ->
     cascaded attention -> output projection, against the same chain in the oracle (fp64
     throughout).  The HIP path rounds q, k, v and the attention output to bf16 on the way, each
@@ -832,9 +887,9 @@ def test_attention_layer_pipeline(mode):
     _, w_out = W.draw_linear(1, width, width, seed=52)
     pool = CascadePool.for_workload(w)
     xt, wq, wo = (Hn.to_torch(a, "bf16") for a in (x_all, w_qkv, w_out))
-    attention_layer(pool, xt[:L], wq, wo, [0], [0], 0, BI)                # block 0 runs alone, becomes clean
+    attention_layer(pool, xt[:L], wq, wo, [0], [0], 0, BI, rotate_q_in_kernel=fused_q)    # block 0 runs alone, becomes clean
     pool.ctx.kv_cache_promote(0)
-    y = attention_layer(pool, xt[L:], wq, wo, [1, 2], [250, 500], 0, mode)
+    y = attention_layer(pool, xt[L:], wq, wo, [1, 2], [250, 500], 0, mode, rotate_q_in_kernel=fused_q)
     torch.cuda.synchronize()
     got = Hn.from_torch(y, "bf16")
     qkv = orc.layer_linear(W.to_f64(x_all), W.to_f64(w_qkv)).reshape(3 * L, 3, H, D)
