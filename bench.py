@@ -124,6 +124,69 @@ def time_attention_only(torch, W, B, w, modes, shares=(), launches=5, pool=None)
     return res
 
 
+def time_layer_iteration(torch, W, w, iterations=4):
+    """One steady-state cascade iteration of a whole self-attention layer at the workload's shape
+    (model width = heads x head_dim, synthetic weights): QKV projection, K/V published, cascaded
+    attention, output projection, then promote / evict / move on.  Two forms: five launches
+    (projection, cache write, Q rotation, attention, projection) and three (the projection's
+    epilogue publishes K/V, the attention kernel rotates Q)."""
+    from paper_2511_20426_amd.runner import CascadePool, attention_layer
+    dev = torch.device("cuda:0")
+    L, H, D, C = w.block_tokens, w.heads, w.head_dim, w.n_inflight
+    width = H * D
+    gen = torch.Generator(device=dev).manual_seed(3)
+    x = torch.randn((C * L, width), generator=gen, device=dev).to(torch.bfloat16)
+    w_qkv = (torch.randn((3 * width, width), generator=gen, device=dev) / width ** 0.5).to(torch.bfloat16)
+    w_out = (torch.randn((width, width), generator=gen, device=dev) / width ** 0.5).to(torch.bfloat16)
+    res = {}
+    for label, kw in (("five_launches", dict(rotate_q_in_kernel=False, publish_in_projection=False)),
+                      ("three_launches", dict(rotate_q_in_kernel=True, publish_in_projection=True))):
+        pool = CascadePool.for_workload(w, device=dev)
+        for g in range(w.n_cached):                       # the clean window: blocks that ran alone
+            attention_layer(pool, x[:L], w_qkv, w_out, [g], [0], 0, 0, **kw)
+            pool.ctx.kv_cache_promote(g)
+        b = w.n_cached
+        ev = []
+        for it in range(iterations + 1):                  # the first iteration warms up
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            attention_layer(pool, x, w_qkv, w_out, list(range(b, b + C)), list(W.TIMESTEPS[::-1][:C]), 0, 0, **kw)
+            pool.ctx.kv_cache_promote(b)
+            pool.ctx.kv_cache_evict(b - w.n_cached)
+            e1.record()
+            b += 1
+            ev.append((e0, e1))
+        torch.cuda.synchronize()
+        ms = sum(a.elapsed_time(c) for a, c in ev[1:]) / iterations
+        flops = w.flops() + 2.0 * C * L * width * (3 * width) + 2.0 * C * L * width * width
+        res[label] = {"ms": ms, "TFLOP/s": flops / ms / 1e9, "frac": flops / ms / 1e9 / PEAK_BF16_TFLOPS}
+        del pool
+    return res
+
+
+def time_streaming_protocol(torch, W, B, w, blocks=13):
+    """The paper's streaming protocol (Sec. 4: rate over the 8th and 9th block of a 13-block
+    rollout) for one attention layer at the workload's shape, driven by the library's scheduler
+    (Alg. 1): cold start, ramp-up, steady state, drain; one untimed pass first."""
+    from paper_2511_20426_amd.runner import CascadePool
+    from paper_2511_20426_amd.rollout import CascadeRollout, streaming_rate
+    dev = torch.device("cuda:0")
+    L, H, D = w.block_tokens, w.heads, w.head_dim
+    gen = torch.Generator(device=dev).manual_seed(w.seed)
+    bank = [tuple((torch.randn((L, H, D), generator=gen, device=dev) * w.input_scale).to(torch.bfloat16)
+                  for _ in range(3)) for _ in range(len(W.TIMESTEPS))]
+    out = {}
+    for rep in range(2):
+        pool = CascadePool.for_workload(w, device=dev)
+        ro = CascadeRollout(pool, blocks, W.TIMESTEPS, lambda g, ti, it, i: bank[i], mode=B.CA_BIDIRECTIONAL, timed=True)
+        recs = ro.run()
+        if rep:
+            out = {"iterations_per_s": streaming_rate(recs), "iteration_ms": [r.ms for r in recs if r.emitted in (7, 8)],
+                   "blocks_per_s_whole_rollout": blocks / (sum(r.ms for r in recs) * 1e-3), "iterations": len(recs)}
+        del ro, pool
+    return out
+
+
 # The projections either side of the attention at the Wan-14B width for five blocks in flight
 # (not part of the default step: --workload linear_qkv_14b / linear_out_14b)
 LINEAR_WORKLOADS = {"linear_qkv_14b": (23400, 15360, 5120), "linear_out_14b": (23400, 5120, 5120)}
@@ -404,6 +467,9 @@ def main() -> int:
                 wv = replace(w, name=f"{w.name}[inflight={ni},cached={nc}]", n_inflight=ni, n_cached=nc)
                 sweep[f"inflight={ni},cached={nc}"] = time_attention_only(torch, W, B, wv, (B.CA_BIDIRECTIONAL,))["bidirectional"]
         result["secondary"]["attention_only"]["cascade_types_14b"] = sweep
+        del pool
+        result["secondary"]["layer_iteration_14b"] = time_layer_iteration(torch, W, w)
+        result["secondary"]["streaming_protocol_14b"] = time_streaming_protocol(torch, W, B, w)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
     print(json.dumps(result))

@@ -240,6 +240,24 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
 int32_t layer_linear_bf16(const void* x_dev, const void* w_dev, void* y_dev, int64_t m_rows, int32_t n_out,
                           int32_t k_in, int64_t ldx, int64_t ldw, int64_t ldy, void* hip_stream);
 
+/* The QKV projection of the blocks in flight and the publication of their K/V (kv_cache_append_batch)
+ * as one launch: the projection's epilogue rotates the K columns and writes K and V straight into
+ * the pages of the blocks' slots, so that neither ever exists as a [token, head, dim] tensor in
+ * HBM (Sec. 3.3: every block's K/V go to the shared pool at every self-attention layer; Alg. 1:
+ * the blocks of an iteration are forwarded together).  x_dev: [n_blocks * L, k_in] activations,
+ * block i's L tokens at rows i*L .., row stride ldx; w_qkv_dev: [3 * heads * 128, k_in], output
+ * rows ordered (q|k|v, head, dim), row stride ldw (the reading stated for layer_linear_bf16).
+ * q_out_dev: [n_blocks * L, heads, 128] contiguous, gets the queries as they leave the projection,
+ * not rotated: cascade_attn_forward_rope takes them as they are.  Metadata as
+ * kv_cache_append_batch: entries NOISY(timestep, epoch), all or none; slots_out optional.
+ * The pool bytes are those that layer_linear_bf16 followed by kv_cache_append_batch on its k and v
+ * columns would write, byte for byte.  bf16 contexts with an even number of heads and k_in a
+ * multiple of 128 (CA_EUNSUPPORTED otherwise); row tiles are counted per block, so the launch
+ * computes ceil(L / 256) * 256 rows per block. */
+int32_t layer_qkv_publish(ca_ctx* ctx, int32_t n_blocks, const int64_t* block_ids, const int32_t* timesteps,
+                          int32_t prompt_epoch, const void* x_dev, int64_t ldx, const void* w_qkv_dev,
+                          int64_t ldw, int32_t k_in, void* q_out_dev, void* hip_stream, int32_t* slots_out);
+
 /* ---- Cascade scheduler: the control flow of Algorithm 1, host integers only.
  * State (b, tau, d) = primary block, timestep index of the primary block, cascade depth.  An
  * iteration forwards blocks b .. b + min(d, G-1), block b+i at timesteps[tau - i] (older blocks

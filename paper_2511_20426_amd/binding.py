@@ -28,7 +28,7 @@ EXPORTS = (
     "kv_cache_evict", "kv_cache_retag", "kv_cache_snapshot", "kv_cache_page_index",
     "rope3d_apply", "rope3d_apply_strided", "cascade_attn_forward", "cascade_attn_forward_share", "cascade_attn_forward_static", "cascade_attn_forward_rope", "ca_debug_visibility", "ca_set_kernel_variant",
     "ca_strerror", "ca_last_device_error",
-    "ca_mfma_microbench", "layer_linear_bf16",
+    "ca_mfma_microbench", "layer_linear_bf16", "layer_qkv_publish",
     "ca_sched_create", "ca_sched_create_lagged", "ca_sched_destroy", "ca_sched_batch", "ca_sched_advance", "ca_sched_state",
 )
 
@@ -123,6 +123,9 @@ def _load() -> C.CDLL:
     lib.ca_mfma_microbench.argtypes = [i32, i32, vp, C.c_size_t, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     lib.layer_linear_bf16.restype = i32
     lib.layer_linear_bf16.argtypes = [vp, vp, vp, i64, i32, i32, i64, i64, i64, vp]
+    lib.layer_qkv_publish.restype = i32
+    lib.layer_qkv_publish.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(i32), i32, vp, i64, vp, i64, i32, vp, vp,
+                                      C.POINTER(i32)]
     lib.ca_sched_create.restype = i32
     lib.ca_sched_create.argtypes = [i64, i32, C.POINTER(i32), i32, C.POINTER(vp)]
     lib.ca_sched_create_lagged.restype = i32
@@ -220,6 +223,18 @@ class Context:
         slots = (C.c_int32 * max(n, 1))()
         _check(lib.kv_cache_append_batch(self._h, n, ids, ts, prompt_epoch, kp, vp, tok_stride, head_stride,
                                          C.c_void_p(stream or None), slots), "kv_cache_append_batch")
+        return [int(slots[i]) for i in range(n)]
+
+    def layer_qkv_publish(self, block_ids: Sequence[int], timesteps: Sequence[int], prompt_epoch: int, x_ptr: int,
+                          ldx: int, w_ptr: int, ldw: int, k_in: int, q_out_ptr: int, stream: int = 0) -> List[int]:
+        n = len(block_ids)
+        assert len(timesteps) == n
+        ids = (C.c_int64 * n)(*block_ids)
+        ts = (C.c_int32 * n)(*timesteps)
+        slots = (C.c_int32 * max(n, 1))()
+        _check(lib.layer_qkv_publish(self._h, n, ids, ts, prompt_epoch, C.c_void_p(x_ptr or None), ldx,
+                                     C.c_void_p(w_ptr or None), ldw, k_in, C.c_void_p(q_out_ptr or None),
+                                     C.c_void_p(stream or None), slots), "layer_qkv_publish")
         return [int(slots[i]) for i in range(n)]
 
     def kv_cache_promote(self, block_id: int) -> None:

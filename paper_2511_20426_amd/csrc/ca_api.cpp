@@ -109,6 +109,37 @@ int32_t kv_cache_append_batch(ca_ctx* ctx, int32_t n_blocks, const int64_t* bloc
   return CA_OK;
 }
 
+int32_t layer_qkv_publish(ca_ctx* ctx, int32_t n_blocks, const int64_t* block_ids, const int32_t* timesteps,
+                          int32_t prompt_epoch, const void* x_dev, int64_t ldx, const void* w_qkv_dev, int64_t ldw,
+                          int32_t k_in, void* q_out_dev, void* hip_stream, int32_t* slots_out) {
+  if (!ctx || !block_ids || !timesteps || n_blocks < 1 || n_blocks > ca::kMaxInflight) return CA_EINVAL;
+  if (!ctx->pool) return CA_ENOPOOL;
+  if (ctx->meta.cfg().dtype != CA_BF16) return CA_EUNSUPPORTED;
+  if (!x_dev || !w_qkv_dev || !q_out_dev) return CA_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(x_dev) | reinterpret_cast<uintptr_t>(w_qkv_dev) |
+       reinterpret_cast<uintptr_t>(q_out_dev)) & 15)
+    return CA_EINVAL;
+  // as kv_cache_append_batch: the entries take effect in order on a copy, all or none
+  ca::CacheMeta next = ctx->meta;
+  int32_t slots[ca::kMaxInflight];
+  int64_t first_frame[ca::kMaxInflight];
+  for (int i = 0; i < n_blocks; ++i) {
+    if (int32_t rc = next.check_append(block_ids[i], &slots[i])) return rc;
+    for (int j = 0; j < i; ++j)
+      if (block_ids[j] == block_ids[i]) return CA_EINVAL;
+    next.commit_append(slots[i], block_ids[i], timesteps[i], prompt_epoch);
+    first_frame[i] = int64_t(next.cfg().frames_per_block) * block_ids[i];
+  }
+  const int32_t rc = ca::launch_gemm_qkv_publish(rope_geom(next), n_blocks, next.block_tokens(), next.pages_per_block(),
+                                                 slots, first_frame, x_dev, ldx, w_qkv_dev, ldw, k_in, q_out_dev,
+                                                 ctx->pool, hip_stream);
+  if (rc != CA_OK) return rc;
+  ctx->meta = next;
+  if (slots_out)
+    for (int i = 0; i < n_blocks; ++i) slots_out[i] = slots[i];
+  return CA_OK;
+}
+
 int32_t kv_cache_promote(ca_ctx* ctx, int64_t block_id) {
   return ctx ? ctx->meta.promote(block_id) : CA_EINVAL;
 }

@@ -121,11 +121,17 @@ int32_t run_mfma_microbench(int data_kind, int trips, void* scratch, size_t scra
                             double* tflops, double* clock_ghz);
 int32_t launch_gemm_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
                          int64_t ldx, int64_t ldw, int64_t ldy, void* stream);
+// The QKV projection of n_blocks blocks (x rows: block b at b * block_tokens; w rows: q|k|v, head,
+// dim) with the publication of K/V to the blocks' slots fused into its epilogue; q_out gets the
+// packed, unrotated queries [n_blocks * block_tokens][heads * 128].
+int32_t launch_gemm_qkv_publish(const RopeGeom& g, int32_t n_blocks, int32_t block_tokens, int32_t pages_per_block,
+                                const int32_t* slot, const int64_t* first_frame, const void* x, int64_t ldx,
+                                const void* w, int64_t ldw, int32_t K, void* q_out, void* pool, void* stream);
 // Per-device facts and one-time kernel attributes, cached for up to kMaxDevices devices (thread
 // safe: the cached values are idempotent and written with relaxed atomics).
 constexpr int kMaxDevices = 64;
 int32_t device_cu_count(int* n_cu);                                   // of the current device
-int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot);  // slot: 0 attention, 1 GEMM, 2 attention rotating Q
+int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot);  // slot: 0 attention, 1 GEMM, 2 attention rotating Q, 3 publishing GEMM
 int32_t finish_launch(const char* what);
 int32_t device_failure(const char* what, int hip_error);   // records the text, clears HIP's last error, returns CA_EDEVICE
 const char* last_device_error();

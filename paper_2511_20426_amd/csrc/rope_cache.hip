@@ -18,62 +18,7 @@
 namespace ca {
 namespace {
 
-struct alignas(16) U4 { uint32_t x, y, z, w; };
-
-// Tensors that pass through once (the unrotated inputs, the rotated output) are read and written
-// with the non-temporal hint, so that they do not displace the pool pages the attention kernel
-// re-reads from the caches.
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_nt;
-__device__ __forceinline__ U4 load_once(const void* p) {
-  const u32x4_nt t = __builtin_nontemporal_load(static_cast<const u32x4_nt*>(p));
-  return U4{t[0], t[1], t[2], t[3]};
-}
-__device__ __forceinline__ void store_once(void* p, const U4& a) {
-  const u32x4_nt t = {a.x, a.y, a.z, a.w};
-  __builtin_nontemporal_store(t, static_cast<u32x4_nt*>(p));
-}
-
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
-
-// fp32 -> bf16 bits, round to nearest even (finite inputs).
-__device__ __forceinline__ uint32_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return f2bf(lo) | (f2bf(hi) << 16); }
-
-struct TokenPos { int f, y, x; };
-
-__device__ __forceinline__ TokenPos token_pos(int64_t n, int64_t first_frame, int gh, int gw) {
-  const int plane = gh * gw;
-  TokenPos p;
-  p.f = int(first_frame + n / plane);
-  const int r = int(n % plane);
-  p.y = r / gw;
-  p.x = r % gw;
-  return p;
-}
-
-// cos/sin of pair `pair` at a token position.  The angle pos * freq is formed and reduced to
-// [-pi, pi] in fp64 (exact to ~1e-15 for any position).  FP64_TRIG evaluates sin/cos in fp64 (fp32
-// storage: results correctly rounded to fp32); otherwise in fp32 on the reduced angle, whose error
-// (~1e-7) is far below the bf16 rounding (4e-3) of what it multiplies, at a fraction of the cost.
-template <bool FP64_TRIG>
-__device__ __forceinline__ void pair_cs(const RopeGeom& g, const TokenPos& p, int pair, float* c, float* s) {
-  const int pos = pair < g.pairs_t ? p.f : (pair < g.pairs_t + g.pairs_h ? p.y : p.x);
-  const double ang = double(pos) * g.freq[pair];
-  if (FP64_TRIG) {
-    double sd, cd;
-    sincos(ang, &sd, &cd);
-    *c = float(cd);
-    *s = float(sd);
-  } else {
-    const double turns = rint(ang * 0.15915494309189535);                 // nearest multiple of 2 pi
-    const float r = float(fma(turns, -6.283185307179586, ang));
-    sincosf(r, s, c);
-  }
-}
+#include "rope_device.hpp"
 
 // ----------------------------------------------------------------------------- generic path
 // One thread owns 4 consecutive pairs (8 elements) of one token and walks a range of heads; the 64
@@ -81,43 +26,6 @@ __device__ __forceinline__ void pair_cs(const RopeGeom& g, const TokenPos& p, in
 // contiguous memory per load when heads are adjacent in memory.
 // MODE 0: y[token][head][dim] (rope3d_apply).  MODE 1: K/V pages of the fp32 pool layout
 // (row-major [token][dim] pages), V copied unrotated.
-template <typename T> struct Vec8;
-template <> struct Vec8<float> {
-  float v[8];
-  __device__ void load(const float* p) {
-    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-  }
-  __device__ void store(float* p) const {
-    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
-    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
-  }
-};
-template <> struct Vec8<uint16_t> {
-  float v[8];
-  __device__ void load(const uint16_t* p) {
-    const U4 a = load_once(p);
-    v[0] = bf16_lo(a.x); v[1] = bf16_hi(a.x); v[2] = bf16_lo(a.y); v[3] = bf16_hi(a.y);
-    v[4] = bf16_lo(a.z); v[5] = bf16_hi(a.z); v[6] = bf16_lo(a.w); v[7] = bf16_hi(a.w);
-  }
-  __device__ void store(uint16_t* p) const {
-    U4 a;
-    a.x = pack_bf16(v[0], v[1]); a.y = pack_bf16(v[2], v[3]);
-    a.z = pack_bf16(v[4], v[5]); a.w = pack_bf16(v[6], v[7]);
-    store_once(p, a);
-  }
-};
-
-template <typename T>
-__device__ __forceinline__ void rotate8(Vec8<T>& x, const float* c, const float* s) {
-#pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const float u = x.v[2 * j], w = x.v[2 * j + 1];
-    x.v[2 * j] = fmaf(u, c[j], -(w * s[j]));
-    x.v[2 * j + 1] = fmaf(u, s[j], w * c[j]);
-  }
-}
-
 struct GenericArgs {
   const void* x;        // MODE 0: input; MODE 1: K
   const void* v;        // MODE 1: V
@@ -177,14 +85,6 @@ __global__ __launch_bounds__(256) void rope_generic_kernel(RopeGeom g, GenericAr
 constexpr int kPage = 128;
 constexpr int kVRowWords = 65;
 
-// cos/sin are shared by every head of a token and, per axis, by every token with the same frame,
-// row or column: a workgroup tabulates them once per axis value present in its page (for a
-// 128-token page of a 30 x 52 grid: 2 frames x 22 pairs + 4 rows x 21 + 52 columns x 21 = 1220
-// evaluations instead of 128 tokens x 64 pairs = 8192) and its threads pick theirs from LDS.
-struct TrigTable {
-  int32_t n_f, n_y, n_x;       // axis values tabulated: consecutive frames / rows (mod grid_h) / columns (mod grid_w)
-};
-
 struct PagedBlock {            // one block of a launch (grid.z picks it)
   const uint16_t* k;
   const uint16_t* v;
@@ -229,44 +129,14 @@ __global__ __launch_bounds__(256) void cache_write_bf16_kernel(RopeGeom g, Paged
   // cos/sin of this thread's 4 pairs at its 8 tokens
   float cs[8][4], sn[8][4];
   if (a.tab.n_f > 0) {
-    const int pairs_w = g.head_dim / 2 - g.pairs_t - g.pairs_h;
-    const TokenPos first = token_pos(min(tok0, a.block_tokens - 1), a.first_frame, g.grid_h, g.grid_w);
-    const int off_y = a.tab.n_f * g.pairs_t, off_x = off_y + a.tab.n_y * g.pairs_h;
-    const int total = off_x + a.tab.n_x * pairs_w;
-    for (int e = t; e < total; e += 256) {
-      TokenPos p = first;
-      int pair;
-      if (e < off_y) {
-        p.f = first.f + e / g.pairs_t;
-        pair = e % g.pairs_t;
-      } else if (e < off_x) {
-        p.y = (first.y + (e - off_y) / g.pairs_h) % g.grid_h;
-        pair = g.pairs_t + (e - off_y) % g.pairs_h;
-      } else {
-        p.x = (first.x + (e - off_x) / pairs_w) % g.grid_w;
-        pair = g.pairs_t + g.pairs_h + (e - off_x) % pairs_w;
-      }
-      float cv, sv;
-      pair_cs<false>(g, p, pair, &cv, &sv);
-      trig[e] = make_float2(cv, sv);
-    }
+    const TrigLayout lay = trig_layout(g, a.tab, tok0, a.block_tokens, a.first_frame);
+    trig_fill(g, lay, trig, t, 256);
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int n = tok0 + r0 + 16 * i;
       const TokenPos p = token_pos(min(n, a.block_tokens - 1), a.first_frame, g.grid_h, g.grid_w);
-      const int rf = p.f - first.f;
-      const int ry = (p.y - first.y + g.grid_h) % g.grid_h, rx = (p.x - first.x + g.grid_w) % g.grid_w;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int pair = c * 4 + j;
-        const int e = pair < g.pairs_t ? rf * g.pairs_t + pair
-                      : (pair < g.pairs_t + g.pairs_h ? off_y + ry * g.pairs_h + (pair - g.pairs_t)
-                                                      : off_x + rx * pairs_w + (pair - g.pairs_t - g.pairs_h));
-        const float2 v = trig[e];
-        cs[i][j] = v.x;
-        sn[i][j] = v.y;
-      }
+      trig_pick(g, lay, trig, p, c, cs[i], sn[i]);
     }
   } else {
 #pragma unroll
@@ -348,7 +218,7 @@ const char* last_device_error() { return g_last_error; }
 
 namespace {
 std::atomic<int> g_cu_count[kMaxDevices];
-std::atomic<int> g_lds_set[3][kMaxDevices];
+std::atomic<int> g_lds_set[4][kMaxDevices];
 }  // namespace
 
 int32_t device_cu_count(int* n_cu) {
@@ -426,19 +296,8 @@ int32_t launch_cache_write(const RopeGeom& g, int dtype, int32_t n_blocks, const
     a.heads_per_group = (g.heads + groups - 1) / groups;
     const dim3 grid((unsigned)pages_per_block,
                     (unsigned)((g.heads + a.heads_per_group - 1) / a.heads_per_group), (unsigned)n_blocks);
-    // axis values a 128-token page can touch: consecutive tokens, so consecutive columns (all of
-    // them once the page is longer than a row), rows and frames
-    const int plane = g.grid_h * g.grid_w;
-    TrigTable tab;
-    tab.n_x = g.grid_w < kPage ? g.grid_w : kPage;
-    tab.n_y = kPage / g.grid_w + 2 < g.grid_h ? kPage / g.grid_w + 2 : g.grid_h;
-    tab.n_f = kPage / plane + 2;
-    const int pairs_w = g.head_dim / 2 - g.pairs_t - g.pairs_h;
-    size_t tab_bytes = sizeof(float2) * (size_t(tab.n_f) * g.pairs_t + size_t(tab.n_y) * g.pairs_h + size_t(tab.n_x) * pairs_w);
-    if (tab_bytes > 16384) {
-      tab.n_f = 0;
-      tab_bytes = 0;
-    }
+    size_t tab_bytes = 0;
+    const TrigTable tab = trig_table_for(g, kPage, 16384, &tab_bytes);
     a.tab = tab;
     hipLaunchKernelGGL(cache_write_bf16_kernel, grid, dim3(256), tab_bytes, s, g, a);
   } else {

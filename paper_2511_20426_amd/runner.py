@@ -119,6 +119,24 @@ def _forward_rope(self, q_raw: torch.Tensor, inflight: Sequence[int], mode: int,
 CascadePool.forward_rope = _forward_rope
 
 
+def _qkv_publish(self, x: torch.Tensor, w_qkv: torch.Tensor, block_ids: Sequence[int], timesteps: Sequence[int],
+                 epoch: int, q_out: torch.Tensor | None = None) -> torch.Tensor:
+    """QKV projection of the blocks in flight with their K/V published to the pool by the same
+    launch (layer_qkv_publish); returns the packed, unrotated queries [C*L, H, D]."""
+    n = len(block_ids) * self.block_tokens
+    width = self.heads * self.head_dim
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.dim() == 2 and x.shape[0] == n and x.stride(1) == 1
+    assert w_qkv.shape == (3 * width, x.shape[1]) and w_qkv.stride(1) == 1 and w_qkv.dtype == torch.bfloat16
+    q = torch.empty((n, self.heads, self.head_dim), dtype=torch.bfloat16, device=x.device) if q_out is None else q_out
+    assert q.is_contiguous() and q.shape == (n, self.heads, self.head_dim)
+    self.ctx.layer_qkv_publish(list(block_ids), list(timesteps), epoch, x.data_ptr(), x.stride(0), w_qkv.data_ptr(),
+                               w_qkv.stride(0), x.shape[1], q.data_ptr(), self._stream())
+    return q
+
+
+CascadePool.qkv_publish = _qkv_publish
+
+
 def linear(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
     """y = x @ w.T through layer_linear_bf16: x [M, K], w [N, K], y [M, N], bf16, rows may be
     strided (last dimension contiguous)."""
@@ -133,17 +151,23 @@ def linear(x: torch.Tensor, w: torch.Tensor, out: torch.Tensor | None = None) ->
 
 def attention_layer(pool: CascadePool, x: torch.Tensor, w_qkv: torch.Tensor, w_out: torch.Tensor,
                     inflight: Sequence[int], timesteps: Sequence[int], epoch: int, mode: int,
-                    rotate_q_in_kernel: bool = True) -> torch.Tensor:
+                    rotate_q_in_kernel: bool = True, publish_in_projection: bool = False) -> torch.Tensor:
     """One self-attention layer around the shared pool, for the blocks in flight (oldest first,
     consecutive in the video): QKV projection, K/V of every block published to the cache, Q
     rotated, cascaded attention, output projection.  x [C*L, width], w_qkv [3*width, width] with
     output rows ordered (q|k|v, head, dim), w_out [width, width]; width = heads * head_dim.
     Library calls only; the q/k/v handed on are strided views of the projection's output.  The
     queries go to the attention kernel as they are (it rotates them while loading), or, with
-    rotate_q_in_kernel=False, through rope3d_apply into a contiguous tensor first."""
+    rotate_q_in_kernel=False, through rope3d_apply into a contiguous tensor first.  With
+    publish_in_projection the first two steps are one launch (layer_qkv_publish): K/V go from the
+    projection's epilogue straight into pool pages; three launches per layer in all."""
     L, H, D = pool.block_tokens, pool.heads, pool.head_dim
     n = len(inflight) * L
     assert x.shape == (n, H * D) and w_qkv.shape == (3 * H * D, H * D) and w_out.shape == (H * D, H * D)
+    if publish_in_projection:
+        q = pool.qkv_publish(x, w_qkv, inflight, timesteps, epoch)
+        o = pool.forward_rope(q, inflight, mode)
+        return linear(o.view(n, H * D), w_out)
     qkv = linear(x, w_qkv).view(n, 3, H, D)
     blocks = [qkv[i * L:(i + 1) * L] for i in range(len(inflight))]
     pool.append_batch(inflight, timesteps, epoch, [b[:, 1] for b in blocks], [b[:, 2] for b in blocks])

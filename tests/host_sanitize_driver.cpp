@@ -61,6 +61,15 @@ int32_t launch_gemm_bf16(const void*, const void*, void*, int64_t, int32_t n, in
                          void*) {
   return (n % 256 || k % 128) ? CA_EUNSUPPORTED : CA_OK;
 }
+int32_t launch_gemm_qkv_publish(const RopeGeom& g, int32_t n_blocks, int32_t block_tokens, int32_t pages, const int32_t* slot,
+                                const int64_t* first_frame, const void* x, int64_t ldx, const void* w, int64_t, int32_t k,
+                                void* q_out, void* pool, void*) {
+  ++g_launches;
+  if (g.heads % 2 || k % 128) return CA_EUNSUPPORTED;
+  for (int i = 0; i < n_blocks; ++i)
+    if (slot[i] < 0 || first_frame[i] < 0) return CA_EDEVICE;
+  return x && w && q_out && pool && ldx >= k && block_tokens > 0 && pages > 0 ? CA_OK : CA_EDEVICE;
+}
 const char* last_device_error() { return ""; }
 
 }  // namespace ca

@@ -858,6 +858,82 @@ def test_layer_linear_rejects_unsupported_shapes():
     assert bool((t == 3.0).all())
 
 
+@pytest.mark.parametrize("heads,fpb,gh,gw,ids,k_in", [(2, 3, 6, 9, (3, 4, 5), 256), (4, 3, 19, 27, (0, 1), 512),
+                                                      (2, 1, 16, 16, (7,), 128), (2, 1, 223, 1, (2, 3), 256),
+                                                      (40, 3, 30, 52, (6, 7, 8, 9, 10), 5120)])
+def test_qkv_publish_writes_the_same_pool_bytes(heads, fpb, gh, gw, ids, k_in):
+    """layer_qkv_publish (projection with K/V published by its epilogue) against layer_linear_bf16
+    followed by kv_cache_append_batch on the k and v columns: the page area of the two pools must
+    be identical byte for byte, the queries identical to the q columns, the metadata the same.
+    Shapes: ragged last pages and row tiles, a row tile whose second half lies past the block's
+    last page (1539 = 6 * 256 + 3), a block of exactly two pages, a geometry too large for the
+    kernel's trig table (223 x 1), and the Wan-14B projection of five blocks."""
+    import torch
+    from paper_2511_20426_amd.runner import CascadePool, linear
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=heads, frames_per_block=fpb, grid_h=gh, grid_w=gw,
+                        sink_blocks=0)
+    L, H, D = w.block_tokens, w.heads, w.head_dim
+    n = len(ids) * L
+    _say(f"qkv publish: heads={H} L={L} blocks={ids} k_in={k_in}")
+    x, wq = W.draw_linear(n, 3 * H * D, k_in, seed=61)
+    xt, wt = Hn.to_torch(x, "bf16"), Hn.to_torch(wq, "bf16")
+    two, one = CascadePool.for_workload(w), CascadePool.for_workload(w)
+    pages = two.pool.numel() - (256 * 256 * 132 * 4)        # the partial-result area behind the pages is not compared
+    two.pool.fill_(0xAB); one.pool.fill_(0xAB)              # stale bytes: every page byte of the blocks must be written
+    ts = [250 * (i + 1) for i in range(len(ids))]
+    qkv = linear(xt, wt).view(n, 3, H, D)
+    two.append_batch(list(ids), ts, 1, [qkv[i * L:(i + 1) * L, 1] for i in range(len(ids))],
+                     [qkv[i * L:(i + 1) * L, 2] for i in range(len(ids))])
+    q = one.qkv_publish(xt, wt, list(ids), ts, 1, q_out=torch.full((n, H, D), float("nan"), dtype=torch.bfloat16,
+                                                                    device="cuda:0"))
+    torch.cuda.synchronize()
+    assert [s.astuple() for s in one.ctx.kv_cache_snapshot()] == [s.astuple() for s in two.ctx.kv_cache_snapshot()]
+    assert torch.equal(q.view(torch.int16), qkv[:, 0].contiguous().view(torch.int16))
+    assert torch.equal(one.pool[:pages], two.pool[:pages])
+    assert bool((one.pool[:pages] != 0xAB).any())
+    # and the k columns really are what the oracle's projection and rotation give (sampled block, head 0 and H-1)
+    if n * k_in < 5e6:
+        kf = orc.layer_linear(W.to_f64(x), W.to_f64(wq)).reshape(n, 3, H, D)[:, 1]
+        raw = one.pool.cpu().numpy()
+        for i, g in enumerate(ids):
+            kr = orc.rope3d(kf[i * L:(i + 1) * L], orc.token_positions(g, fpb, gh, gw), w.rope_dims, w.rope_theta)
+            for h in (0, H - 1):
+                for p in (0, w.pages_per_block - 1):
+                    Kp, _ = Hn.decode_bf16_pages(raw, one.ctx.kv_cache_page_index(g, p, h))
+                    nv = min(128, L - 128 * p)
+                    ref = kr[128 * p:128 * p + nv, h]
+                    # two roundings to bf16 (projection result, rotated value) of values of order max|k|
+                    assert (np.abs(W.bf16_bits_to_f32(Kp[:nv]) - ref) <= 2.0 ** -7 * np.abs(kf[i * L:(i + 1) * L, h]).max()).all()
+                    assert not Kp[nv:].any()
+
+
+def test_qkv_publish_rejects_what_it_does_not_cover():
+    import torch
+    from paper_2511_20426_amd import binding as B
+    from paper_2511_20426_amd.runner import CascadePool
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=3, grid_h=4, grid_w=5)
+    pool = CascadePool.for_workload(w)
+    x = torch.zeros((w.block_tokens, 384), dtype=torch.bfloat16, device="cuda:0")
+    wq = torch.zeros((3 * 384, 384), dtype=torch.bfloat16, device="cuda:0")
+    before = [s.astuple() for s in pool.ctx.kv_cache_snapshot()]
+    with pytest.raises(B.CascadeAttnError) as e:                     # an odd number of heads: a column tile would straddle q|k|v
+        pool.qkv_publish(x, wq, [0], [0], 0)
+    assert e.value.code == B.CA_EUNSUPPORTED
+    assert [s.astuple() for s in pool.ctx.kv_cache_snapshot()] == before          # nothing was tagged
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=2, grid_h=4, grid_w=5)
+    pool = CascadePool.for_workload(w)
+    x = torch.zeros((w.block_tokens, 256), dtype=torch.bfloat16, device="cuda:0")
+    wq = torch.zeros((768, 256), dtype=torch.bfloat16, device="cuda:0")
+    pool.qkv_publish(x, wq, [0], [0], 0)
+    pool.ctx.kv_cache_promote(0)
+    with pytest.raises(B.CascadeAttnError) as e:                     # a clean block is not rewritten
+        pool.qkv_publish(x, wq, [0], [0], 0)
+    assert e.value.code == B.CA_ESTATE
+    with pytest.raises(B.CascadeAttnError) as e:                     # k_in not a multiple of 128
+        pool.ctx.layer_qkv_publish([1], [0], 0, x.data_ptr(), 256, wq.data_ptr(), 256, 192, x.data_ptr())
+    assert e.value.code == B.CA_EUNSUPPORTED
+
+
 def test_empty_rotation_is_a_no_op():
     import torch
     from paper_2511_20426_amd.runner import CascadePool
@@ -870,11 +946,12 @@ def test_empty_rotation_is_a_no_op():
     assert bool((x == 2.0).all())
 
 
-@pytest.mark.parametrize("fused_q", [True, False])
+@pytest.mark.parametrize("fused_q,publish", [(True, False), (False, False), (True, True)])
 @pytest.mark.parametrize("mode", [BI, CA])
-def test_attention_layer_pipeline(mode, fused_q):
-    """QKV projection -> K/V published + Q rotated (strided views of the projection's output) ->
-    cascaded attention -> output projection, against the same chain in the oracle (fp64
+def test_attention_layer_pipeline(mode, fused_q, publish):
+    """QKV projection -> K/V published + Q rotated (strided views of the projection's output; or Q
+    rotated by the attention kernel; or, with publish, K/V published by the projection's own
+    epilogue: three launches per layer) -> cascaded attention -> output projection, against the same chain in the oracle (fp64
     throughout).  The HIP path rounds q, k, v and the attention output to bf16 on the way, each
     2^-9 relative, so the bar is looser than for one stage: relative L2 1e-2 (measured 4.6e-3)."""
     import torch
@@ -887,9 +964,10 @@ def test_attention_layer_pipeline(mode, fused_q):
     _, w_out = W.draw_linear(1, width, width, seed=52)
     pool = CascadePool.for_workload(w)
     xt, wq, wo = (Hn.to_torch(a, "bf16") for a in (x_all, w_qkv, w_out))
-    attention_layer(pool, xt[:L], wq, wo, [0], [0], 0, BI, rotate_q_in_kernel=fused_q)    # block 0 runs alone, becomes clean
+    kw = dict(rotate_q_in_kernel=fused_q, publish_in_projection=publish)
+    attention_layer(pool, xt[:L], wq, wo, [0], [0], 0, BI, **kw)          # block 0 runs alone, becomes clean
     pool.ctx.kv_cache_promote(0)
-    y = attention_layer(pool, xt[L:], wq, wo, [1, 2], [250, 500], 0, mode, rotate_q_in_kernel=fused_q)
+    y = attention_layer(pool, xt[L:], wq, wo, [1, 2], [250, 500], 0, mode, **kw)
     torch.cuda.synchronize()
     got = Hn.from_torch(y, "bf16")
     qkv = orc.layer_linear(W.to_f64(x_all), W.to_f64(w_qkv)).reshape(3 * L, 3, H, D)
