@@ -173,12 +173,13 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
     }
     __syncthreads();
     if (!has_page) return;
+    // the lane's rows are tokens tok0 + r4 + 4 it: positions move on by four tokens per trip
+    TokenPos p = token_pos(min(tok0 + r4, a.block_rows - 1), pb.first_frame[blk], pb.g.grid_h, pb.g.grid_w);
 #pragma unroll 2
-    for (int it = 0; it < 32; ++it) {
+    for (int it = 0; it < 32; ++it, p = token_advance(p, 4, pb.g.grid_h, pb.g.grid_w)) {
       const int row = it * 4 + r4;
       U4 kk = {0, 0, 0, 0};
       if (tok0 + row < a.block_rows) {
-        const TokenPos p = token_pos(tok0 + row, pb.first_frame[blk], pb.g.grid_h, pb.g.grid_w);
         float cs[4], sn[4];
         if (pb.tab.n_f > 0) {
           trig_pick(pb.g, lay, trig, p, c, cs, sn);

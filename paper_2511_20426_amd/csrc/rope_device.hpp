@@ -102,6 +102,20 @@ __device__ __forceinline__ void rotate8(Vec8<T>& x, const float* c, const float*
 // row or column: a workgroup tabulates them once per axis value present in a 128-token page (for
 // a 30 x 52 grid: 2 frames x 22 pairs + 4 rows x 21 + 52 columns x 21 = 1220 evaluations instead
 // of 128 tokens x 64 pairs = 8192) and its threads pick theirs from LDS.
+// the token `step` tokens after p (step >= 0), without the divisions of token_pos
+__device__ __forceinline__ TokenPos token_advance(TokenPos p, int step, int gh, int gw) {
+  p.x += step;
+  while (p.x >= gw) {
+    p.x -= gw;
+    ++p.y;
+  }
+  while (p.y >= gh) {
+    p.y -= gh;
+    ++p.f;
+  }
+  return p;
+}
+
 struct TrigTable {
   int32_t n_f, n_y, n_x;       // axis values tabulated: consecutive frames / rows (mod grid_h) / columns (mod grid_w)
 };
@@ -147,7 +161,9 @@ __device__ __forceinline__ void trig_fill(const RopeGeom& g, const TrigLayout& l
 __device__ __forceinline__ void trig_pick(const RopeGeom& g, const TrigLayout& l, const float2* trig, const TokenPos& p,
                                           int c, float* cs, float* sn) {
   const int rf = p.f - l.first.f;
-  const int ry = (p.y - l.first.y + g.grid_h) % g.grid_h, rx = (p.x - l.first.x + g.grid_w) % g.grid_w;
+  int ry = p.y - l.first.y, rx = p.x - l.first.x;         // both in (-grid, grid): one conditional add wraps them
+  ry += ry < 0 ? g.grid_h : 0;
+  rx += rx < 0 ? g.grid_w : 0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int pair = c * 4 + j;

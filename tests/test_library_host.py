@@ -191,6 +191,15 @@ def test_error_paths_leave_state_unchanged():
     fails(B.CA_ENOENT, ctx.cascade_attn_forward_share, 0, [0, 2], 0, 1, B.CA_BIDIRECTIONAL, 0)
     for first, count in ((0, 1), (1, 1), (0, 2)):
         fails(B.CA_ENOPOOL, ctx.cascade_attn_forward_share, 0, [0, 1], first, count, B.CA_BLOCK_CAUSAL, 0)
+    # the forward's other forms check the same things in the same order, and all need a pool
+    fails(B.CA_ENOENT, ctx.cascade_attn_forward_static, 0, [0, 2], B.CA_BIDIRECTIONAL, 0)
+    fails(B.CA_ENOPOOL, ctx.cascade_attn_forward_static, 0, [0, 1], B.CA_BIDIRECTIONAL, 0)
+    fails(B.CA_ENOENT, ctx.cascade_attn_forward_rope, 0, 128 * w.heads, 128, [0, 2], B.CA_BIDIRECTIONAL, 0)
+    fails(B.CA_EINVAL, ctx.cascade_attn_forward_rope, 0, 128 * w.heads, 128, [1, 0], B.CA_BIDIRECTIONAL, 0)
+    fails(B.CA_ENOPOOL, ctx.cascade_attn_forward_rope, 0, 128 * w.heads, 128, [0, 1], B.CA_BLOCK_CAUSAL, 0)
+    # the publishing projection changes no tag without a pool to publish to
+    fails(B.CA_ENOPOOL, ctx.layer_qkv_publish, [3], [0], 0, 0, 128, 0, 128, 128, 0)
+    fails(B.CA_EINVAL, ctx.layer_qkv_publish, [], [], 0, 0, 128, 0, 128, 128, 0)
     fails(B.CA_EINVAL, ctx.set_kernel_variant, 12345)
     ctx.set_kernel_variant(1)
     ctx.set_kernel_variant(0)
