@@ -31,6 +31,9 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 constexpr int kTile = 256;
 constexpr int kSbRows = 8, kSbCols = 4;           // tiles of one XCD's block
 constexpr int kEpiRow = 272;                      // bytes per row of a wave's 128 x 128 bf16 tile in LDS
+constexpr int kEpiRowV = 260;                     // the same for a V sub-tile of the publishing epilogue, which is read
+                                                  // back two bytes at a time down its columns: 65 dwords per row spread
+                                                  // the 16 token groups a wave reads at once over 16 banks
 constexpr int kEpiWave = 128 * kEpiRow;
 constexpr int kGemmLds = 160 * 1024;              // main loop: 3 W stages + 2 X stages of 32 KB; epilogue: 4 x kEpiWave
 static_assert(4 * kEpiWave + 2 * 12288 <= kGemmLds, "epilogue staging and two trig tables fit");
@@ -118,6 +121,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
   // Pair p of MFMA tile T = 8 ti + tj: n = 16 ti + 4 grp + 2 p, m = 16 tj + l15.
   __syncthreads();                                    // every wave is done with the stage buffers
   uint8_t* mine = lds + wave * kEpiWave;
+  const int v_section = kPublish && (n0 + wn * 128) / (a.pub.heads * 128) == 2;
+  const int pitch = v_section ? kEpiRowV : kEpiRow;
   const u32x16 o[8] = {o0, o1, o2, o3, o4, o5, o6, o7};
 #pragma unroll
   for (int T = 0; T < 64; ++T) {
@@ -126,7 +131,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
     for (int p = 0; p < 2; ++p) {
       const int n = 16 * ti + 4 * grp + 2 * p;
       const int m = 16 * tj + l15;
-      *reinterpret_cast<uint32_t*>(mine + m * kEpiRow + n * 2) = o[(2 * T + p) >> 4][(2 * T + p) & 15];
+      *reinterpret_cast<uint32_t*>(mine + m * pitch + n * 2) = o[(2 * T + p) >> 4][(2 * T + p) & 15];
     }
   }
   __syncthreads();
@@ -157,7 +162,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
       const int row = it * 4 + r4;
       const u32x4 v = *reinterpret_cast<const u32x4*>(mine + row * kEpiRow + c * 16);
       if (tok0 + row < a.block_rows)
-        *reinterpret_cast<u32x4*>(a.y + int64_t(m0 + wm * 128 + row) * a.ldy + head * 128 + c * 8) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(a.y + int64_t(m0 + wm * 128 + row) * a.ldy + head * 128 + c * 8));
     }
     return;
   }
@@ -195,7 +200,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
         kk.x = pack_bf16(e.v[0], e.v[1]); kk.y = pack_bf16(e.v[2], e.v[3]);
         kk.z = pack_bf16(e.v[4], e.v[5]); kk.w = pack_bf16(e.v[6], e.v[7]);
       }
-      *reinterpret_cast<U4*>(kpage + row * 256 + ((c ^ (row & 15)) << 4)) = kk;
+      store_once(kpage + row * 256 + ((c ^ (row & 15)) << 4), kk);
     }
     return;
   }
@@ -210,13 +215,13 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       const int tok = tb + (j & 3) + 8 * (j >> 2);
-      const uint32_t w = *reinterpret_cast<const uint16_t*>(mine + tok * kEpiRow + d * 2);
+      const uint32_t w = *reinterpret_cast<const uint16_t*>(mine + tok * kEpiRowV + d * 2);
       e[j] = tok0 + tok < a.block_rows ? w : 0u;
     }
     U4 o;
     o.x = e[0] | (e[1] << 16); o.y = e[2] | (e[3] << 16);
     o.z = e[4] | (e[5] << 16); o.w = e[6] | (e[7] << 16);
-    *reinterpret_cast<U4*>(vpage + d * 256 + ((c ^ (d & 15)) << 4)) = o;
+    store_once(vpage + d * 256 + ((c ^ (d & 15)) << 4), o);
   }
 }
 

@@ -22,12 +22,13 @@ __device__ __forceinline__ void store_once(void* p, const U4& a) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs).
-__device__ __forceinline__ uint32_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+// two fp32 -> one dword of bf16 bits, round to nearest even (v_cvt_pk_bf16_f32)
+typedef __attribute__((ext_vector_type(2))) float rd_f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 rd_bf16x2;
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  const rd_f32x2 f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, rd_bf16x2));
 }
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return f2bf(lo) | (f2bf(hi) << 16); }
 
 struct TokenPos { int f, y, x; };
 
