@@ -509,6 +509,51 @@ def test_step_replays_from_a_hip_graph():
         assert bool(out.float().abs().max() > 0)
 
 
+def test_layer_in_three_launches_replays_from_a_hip_graph():
+    """The three-launch layer (projection publishing K/V, attention rotating Q, output projection)
+    captured into a HIP graph after one eager call: replays with fresh activations, eager work in
+    between, must reproduce the eager result bit for bit (the library's device calls are kernel
+    launches only, and its one-time kernel attributes are set by the eager call)."""
+    import torch
+    from paper_2511_20426_amd.runner import CascadePool, linear
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=4, grid_h=12, grid_w=15, n_cached=1, n_inflight=2)
+    L, H, D = w.block_tokens, w.heads, w.head_dim
+    width = H * D
+    x_all, w_qkv = W.draw_linear(3 * L, 3 * width, width, seed=71)
+    _, w_out = W.draw_linear(1, width, width, seed=72)
+    pool = CascadePool.for_workload(w)
+    xt, wq, wo = (Hn.to_torch(a, "bf16") for a in (x_all, w_qkv, w_out))
+    q0 = pool.qkv_publish(xt[:L], wq, [0], [0], 0)                 # block 0 becomes the clean cache
+    pool.ctx.kv_cache_promote(0)
+    x = xt[L:].clone()
+    q = torch.empty((2 * L, H, D), dtype=torch.bfloat16, device="cuda:0")
+    o = torch.empty_like(q)
+    y = torch.empty((2 * L, width), dtype=torch.bfloat16, device="cuda:0")
+
+    def layer():
+        pool.qkv_publish(x, wq, [1, 2], [250, 500], 0, q_out=q)     # the in-flight blocks are rewritten in place
+        pool.forward_rope(q, [1, 2], BI, out=o)
+        linear(o.view(2 * L, width), wo, out=y)
+
+    layer()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        layer()
+    gen = torch.Generator(device="cuda:0").manual_seed(9)
+    for trial in range(3):
+        x.copy_(torch.randn(x.shape, generator=gen, device="cuda:0").to(torch.bfloat16))
+        layer()
+        torch.cuda.synchronize()
+        expect = y.clone()
+        y.zero_(); o.zero_(); q.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), expect.view(torch.int16)), f"replay {trial}"
+        assert bool(y.float().abs().max() > 0)
+
+
 # --------------------------------------------------------------------------- full shapes, sampled rows
 
 def _reordering_bound(a, b, v, keys):
