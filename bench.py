@@ -75,16 +75,16 @@ def cpu_baseline(w, seconds_target=15.0):
     }
 
 
-def time_attention_only(torch, W, B, w, modes, shares=(), launches=5, pool=None):
+def time_attention_only(torch, W, B, w, modes, shares=(), launches=5, prepared=None):
     """Attention launches of workload `w` on a steady-state pool (n_cached clean blocks, the
     in-flight ones appended, Q rotated), timed with events around `launches` forwards after two
     warm-up calls.  Returns {label: {"ms", "TFLOP/s", "frac"}}; `shares`: also one device's share
-    (queries of in-flight block i only) per mode."""
+    (queries of in-flight block i only) per mode.  prepared = (pool, in-flight ids, rotated Q) reuses a
+    pool that is already in that state instead of building one."""
     from paper_2511_20426_amd.runner import CascadePool
     dev = torch.device("cuda:0")
     L, H, D, C = w.block_tokens, w.heads, w.head_dim, w.n_inflight
-    own = pool is None
-    if own:
+    if prepared is None:
         pool = CascadePool.for_workload(w, device=dev)
         gen = torch.Generator(device=dev).manual_seed(w.seed + 1)
         draw = lambda n: (torch.randn((n, H, D), generator=gen, device=dev) * w.input_scale).to(torch.bfloat16)
@@ -96,7 +96,7 @@ def time_attention_only(torch, W, B, w, modes, shares=(), launches=5, pool=None)
         pool.append_batch(infl, list(W.TIMESTEPS[::-1][:C]), 0, kb, vb)
         q_rot = pool.rope(draw(C * L), w.frames_per_block * infl[0])
     else:
-        pool, infl, q_rot = pool
+        pool, infl, q_rot = prepared
     out = torch.empty_like(q_rot)
     res = {}
     cases = [(m, None) for m in modes] + [(m, s) for m in modes for s in shares]
@@ -451,7 +451,7 @@ def main() -> int:
         pool.append_batch(infl, timesteps[:C], 0, k_blocks, v_blocks)
         pool.rope(q, w.frames_per_block * infl[0], out=q_rot)
         result["secondary"]["attention_only"] = {
-            "c4_wan14b_cascade5": time_attention_only(torch, W, B, w, both, shares=(0, C - 1), pool=(pool, infl, q_rot)),
+            "c4_wan14b_cascade5": time_attention_only(torch, W, B, w, both, shares=(0, C - 1), prepared=(pool, infl, q_rot)),
             "c3_wan1p3b_cascade5": time_attention_only(torch, W, B, W.CONFIGS["c3_wan1p3b_cascade5"], both),
             "c2_wan1p3b_seq": time_attention_only(torch, W, B, W.CONFIGS["c2_wan1p3b_seq"], (B.CA_BIDIRECTIONAL,)),
         }

@@ -116,7 +116,6 @@ int32_t launch_attn_bf16_static(const AttnPlan& p, int variant, const void* q, v
                                 void* stream);
 void attn_static_scratch_prepare();
 
-// Launchers end with this: CA_OK, or CA_EDEVICE after recording the HIP error text.
 int32_t run_mfma_microbench(int data_kind, int trips, void* scratch, size_t scratch_bytes, void* stream,
                             double* tflops, double* clock_ghz);
 int32_t launch_gemm_bf16(const void* x, const void* w, void* y, int64_t M, int32_t N, int32_t K,
@@ -132,7 +131,7 @@ int32_t launch_gemm_qkv_publish(const RopeGeom& g, int32_t n_blocks, int32_t blo
 constexpr int kMaxDevices = 64;
 int32_t device_cu_count(int* n_cu);                                   // of the current device
 int32_t ensure_dynamic_lds(const void* kernel, int bytes, int slot);  // slot: 0 attention, 1 GEMM, 2 attention rotating Q, 3 publishing GEMM
-int32_t finish_launch(const char* what);
+int32_t finish_launch(const char* what);   // launchers end with this: CA_OK, or CA_EDEVICE after recording HIP's last error
 int32_t device_failure(const char* what, int hip_error);   // records the text, clears HIP's last error, returns CA_EDEVICE
 const char* last_device_error();
 
