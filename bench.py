@@ -164,6 +164,42 @@ def time_layer_iteration(torch, W, w, iterations=4):
     return res
 
 
+def time_qkv_projection(torch, W, w, launches=10):
+    """The QKV projection of the blocks in flight at the workload's shape (model width = heads x
+    head_dim), three ways: layer_linear_bf16 alone, kv_cache_append_batch on its k and v columns,
+    and layer_qkv_publish, which does both in one launch."""
+    from paper_2511_20426_amd.runner import CascadePool, linear
+    dev = torch.device("cuda:0")
+    L, H, D, C = w.block_tokens, w.heads, w.head_dim, w.n_inflight
+    width, n = H * D, C * L
+    gen = torch.Generator(device=dev).manual_seed(5)
+    x = torch.randn((n, width), generator=gen, device=dev).to(torch.bfloat16)
+    w_qkv = (torch.randn((3 * width, width), generator=gen, device=dev) / width ** 0.5).to(torch.bfloat16)
+    pool = CascadePool.for_workload(w, device=dev)
+    qkv = torch.empty((n, 3, H, D), dtype=torch.bfloat16, device=dev)
+    q = torch.empty((n, H, D), dtype=torch.bfloat16, device=dev)
+    ids, ts = list(range(w.n_cached, w.n_cached + C)), list(W.TIMESTEPS[::-1][:C])
+    ks, vs = [qkv[i * L:(i + 1) * L, 1] for i in range(C)], [qkv[i * L:(i + 1) * L, 2] for i in range(C)]
+    cases = (("layer_linear_bf16", lambda: linear(x, w_qkv, out=qkv.view(n, 3 * width))),
+             ("kv_cache_append_batch", lambda: pool.append_batch(ids, ts, 0, ks, vs)),
+             ("layer_qkv_publish", lambda: pool.qkv_publish(x, w_qkv, ids, ts, 0, q_out=q)))
+    res = {}
+    for label, run in cases:
+        run(); run()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(launches):
+            run()
+        e1.record()
+        torch.cuda.synchronize()
+        res[label] = {"ms": e0.elapsed_time(e1) / launches}
+    flops = 2.0 * n * 3 * width * width
+    for label in ("layer_linear_bf16", "layer_qkv_publish"):
+        res[label]["TFLOP/s"] = flops / res[label]["ms"] / 1e9
+        res[label]["frac"] = res[label]["TFLOP/s"] / PEAK_BF16_TFLOPS
+    return res
+
+
 def time_streaming_protocol(torch, W, B, w, blocks=13):
     """The paper's streaming protocol (Sec. 4: rate over the 8th and 9th block of a 13-block
     rollout) for one attention layer at the workload's shape, driven by the library's scheduler
@@ -469,6 +505,7 @@ def main() -> int:
         result["secondary"]["attention_only"]["cascade_types_14b"] = sweep
         del pool
         result["secondary"]["layer_iteration_14b"] = time_layer_iteration(torch, W, w)
+        result["secondary"]["qkv_projection_14b"] = time_qkv_projection(torch, W, w)
         result["secondary"]["streaming_protocol_14b"] = time_streaming_protocol(torch, W, B, w)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w)
