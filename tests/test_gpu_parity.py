@@ -425,6 +425,37 @@ def test_bf16_largest_configuration(mode, gh, gw):
     Hn.assert_close(_cat(outs), _cat(ref), "bf16", "32 KV blocks, 8 in flight", bound=_cat(bound))
 
 
+def test_bf16_pool_beyond_4_gib():
+    """Page addresses past 4 GiB: 32 slots x 3 pages x 1024 heads x 64 KB = 6.4 GB of pages, the
+    blocks in the last two slots (byte offsets 6.0 and 6.2 GB), checked on the first, a middle and
+    the last head; cache write, both forwards and the page index against the oracle's rule."""
+    w = W.small_variant(W.CONFIGS["c5_wan1p3b_rollout"], heads=1024, grid_h=8, grid_w=12, window_blocks=23,
+                        max_inflight=8, n_cached=1, n_inflight=1)
+    _say(f"pool beyond 4 GiB: heads={w.heads} L={w.block_tokens}")
+    heads = (0, 517, 1023)
+    q, k, v = W.draw_config(w, seed=77)
+    pool = Hn.gpu_setup(w, k, v, [30], [31])
+    assert pool.pool.numel() > (1 << 32)
+    cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, w.max_inflight, w.pages_per_block, w.heads)
+    for g in (30, 31):
+        slot = cache.append(g, 0, 0)
+        for h in heads:
+            idx = cache.page_index(slot, w.pages_per_block - 1, h)
+            assert idx == pool.ctx.kv_cache_page_index(g, w.pages_per_block - 1, h)
+    assert cache.page_index(cache.slot_of(31), 0, 0) * 65536 > (1 << 32)
+    ref, bound = (_cat(x) for x in Hn.oracle_forward_bounded(w, q, k, v, [30], [31], BI, heads=heads))
+    for got in (Hn.gpu_forward(w, pool, q, [31], BI), Hn.gpu_forward_rope(w, pool, q, [31], BI)):
+        assert np.isfinite(got).all()
+        Hn.assert_close(got[:, list(heads)], ref, "bf16", "pool beyond 4 GiB", bound=bound)
+    # the V page of the last head of the last slot holds that head's V, bit for bit
+    import torch
+    L = w.block_tokens
+    idx = pool.ctx.kv_cache_page_index(31, 0, 1023)
+    raw = pool.pool[idx * 65536:(idx + 1) * 65536].cpu().numpy()
+    _, Vp = Hn.decode_bf16_pages(raw, 0)
+    np.testing.assert_array_equal(Vp, v[L:L + 128, 1023])
+
+
 def test_bf16_single_block_modes_agree_bitwise():
     """One in-flight block: both modes are the same computation (cascade P1, Fig. 7)."""
     w = W.small_variant(W.CONFIGS["c2_wan1p3b_seq"], heads=2, grid_h=9, grid_w=14, n_cached=3)
