@@ -51,6 +51,31 @@ def test_static_scratch_forward_matches_the_pool_scratch_forward_twice_in_a_row(
     del first, second
 
 
+def test_static_scratch_forward_replays_from_a_hip_graph():
+    """What the call is for: after one eager call on the device it records into a HIP graph as
+    plain kernel launches, and every replay reproduces the eager result bit for bit."""
+    import torch
+    w = W.small_variant(W.CONFIGS["c3_wan1p3b_cascade5"], heads=16, grid_h=19, grid_w=27, n_cached=1, n_inflight=3)
+    q, k, v = W.draw_config(w, seed=83)
+    pool = Hn.gpu_setup(w, k, v, [0], [1, 2, 3])
+    qr = pool.rope(Hn.to_torch(q, w.dtype), w.frames_per_block * 1)
+    out = torch.empty_like(qr)
+    pool.forward(qr, [1, 2, 3], orc.BIDIRECTIONAL, out=out, static_scratch=True)        # eager: one-time set-up happens here
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pool.forward(qr, [1, 2, 3], orc.BIDIRECTIONAL, out=out, static_scratch=True)
+    gen = torch.Generator(device="cuda:0").manual_seed(4)
+    for trial in range(3):
+        qr.copy_((torch.randn(qr.shape, generator=gen, device="cuda:0") * 0.5).to(torch.bfloat16))
+        expect = pool.forward(qr, [1, 2, 3], orc.BIDIRECTIONAL, out=torch.empty_like(qr))   # partials in the pool
+        torch.cuda.synchronize()
+        out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), expect.view(torch.int16)), f"replay {trial}"
+
+
 def test_static_scratch_forward_fp32_context_is_the_plain_forward():
     import torch
     w = W.CONFIGS["c1_tiny_f32"]
