@@ -53,6 +53,10 @@ class CascadeRollout:
     # post_fn(o) (e.g. the output projection)
     batch_qkv_fn: Optional[Callable] = None
     post_fn: Optional[Callable] = None
+    # publish_fn(batch, epoch) -> packed unrotated queries [n * L, H, D]: publishes the batch's K/V
+    # itself (layer_qkv_publish: one launch for projection and cache write); the queries then go to
+    # the attention kernel as they are (cascade_attn_forward_rope).  Replaces qkv_fn / batch_qkv_fn.
+    publish_fn: Optional[Callable] = None
     mode: int = B.CA_BIDIRECTIONAL
     window_blocks: Optional[int] = None        # clean blocks kept; default: the pool's window
     epoch: int = 0
@@ -84,24 +88,28 @@ class CascadeRollout:
         it = self.sched.state()[3]
         if self.timed:
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        if self.batch_qkv_fn is None:
+        if self.batch_qkv_fn is None and self.publish_fn is None:
             staged = [self.qkv_fn(g, ti, it, i) for i, (g, ti, _) in enumerate(batch)]
         if self.timed:
             e0.record()
-        if self.batch_qkv_fn is not None:
-            staged = self.batch_qkv_fn(batch)
         n = len(batch)
-        ks, vs = [s[1] for s in staged], [s[2] for s in staged]
-        if all(t.stride() == ks[0].stride() for t in ks + vs):
-            pool.append_batch([g for g, _, _ in batch], [t for _, _, t in batch], self.epoch, ks, vs)
-        else:                                  # one launch needs one set of strides
-            for (g, ti, t), k, v in zip(batch, ks, vs):
-                pool.append(g, t, self.epoch, k, v)
-        for i, ((g, ti, t), (q, k, v)) in enumerate(zip(batch, staged)):
-            # each block's queries are rotated from wherever they live into the packed tensor
-            pool.rope(q, pool.frames_per_block * g, out=self._qr[i * L:(i + 1) * L])
         infl = [g for g, _, _ in batch]
-        o = pool.forward(self._qr[:n * L], infl, self.mode, out=self._o[:n * L])
+        if self.publish_fn is not None:
+            q = self.publish_fn(batch, self.epoch)
+            o = pool.forward_rope(q[:n * L], infl, self.mode, out=self._o[:n * L])
+        else:
+            if self.batch_qkv_fn is not None:
+                staged = self.batch_qkv_fn(batch)
+            ks, vs = [s[1] for s in staged], [s[2] for s in staged]
+            if all(t.stride() == ks[0].stride() for t in ks + vs):
+                pool.append_batch(infl, [t for _, _, t in batch], self.epoch, ks, vs)
+            else:                                  # one launch needs one set of strides
+                for (g, ti, t), k, v in zip(batch, ks, vs):
+                    pool.append(g, t, self.epoch, k, v)
+            for i, ((g, ti, t), (q, k, v)) in enumerate(zip(batch, staged)):
+                # each block's queries are rotated from wherever they live into the packed tensor
+                pool.rope(q, pool.frames_per_block * g, out=self._qr[i * L:(i + 1) * L])
+            o = pool.forward(self._qr[:n * L], infl, self.mode, out=self._o[:n * L])
         if self.post_fn is not None:
             self.post_fn(o)
         emitted, completed = self.sched.advance()
@@ -160,6 +168,9 @@ def main(argv=None) -> None:
                          "P1..P4 (default: Alg. 1 = 1)")
     ap.add_argument("--layer", action="store_true",
                     help="include the QKV and output projections (synthetic weights) in every iteration")
+    ap.add_argument("--three-launches", action="store_true",
+                    help="with --layer: the projection publishes K/V itself and the attention kernel rotates Q "
+                         "(layer_qkv_publish, cascade_attn_forward_rope) instead of five launches per iteration")
     a = ap.parse_args(argv)
     w = W.CONFIGS[a.workload]
     dev = torch.device("cuda:0")
@@ -192,10 +203,23 @@ def main(argv=None) -> None:
             n = o.shape[0]
             linear(o.view(n, width), w_out, out=y[:n])
 
-        hooks = dict(batch_qkv_fn=batch_qkv_fn, post_fn=post_fn)
+        q_packed = torch.empty((len(W.TIMESTEPS) * L, H, D), dtype=torch.bfloat16, device=dev)
+        current = {}
+
+        def publish_fn(batch, epoch):
+            n = len(batch) * L
+            return current["pool"].qkv_publish(x[:n], w_qkv, [g for g, _, _ in batch], [t for _, _, t in batch], epoch,
+                                               q_out=q_packed[:n])
+
+        if a.three_launches:
+            hooks = dict(publish_fn=publish_fn, post_fn=post_fn)
+        else:
+            hooks = dict(batch_qkv_fn=batch_qkv_fn, post_fn=post_fn)
     rates, steady_ms = [], []
     for rep in range(a.repeats + 1):                      # first pass warms up
         pool = CascadePool.for_workload(pool_w)
+        if a.layer:
+            current["pool"] = pool
         ro = CascadeRollout(pool, a.blocks, W.TIMESTEPS, lambda g, ti, it, i: bank[i], mode=mode, timed=True, lag=a.lag, **hooks)
         recs = ro.run()
         if rep:
@@ -206,7 +230,7 @@ def main(argv=None) -> None:
     print(json.dumps({
         "metric": "steady_state_cascade_iterations_per_s", "value": sum(rates) / len(rates),
         "unit": "iterations/s (one attention layer%s; one block of 3 latent frames emitted per iteration)"
-                % (" with its QKV and output projections" if a.layer else ""),
+                % ((" with its QKV and output projections" + (", three launches" if a.three_launches else "")) if a.layer else ""),
         "protocol": "mean over the iterations emitting the 8th and 9th block of a %d-block rollout" % a.blocks,
         "workload": w.name, "mode": a.mode, "clean_window_blocks": window, "lag": a.lag or 1,
         "blocks_per_s": a.blocks / (sum(r.ms for r in recs) * 1e-3),

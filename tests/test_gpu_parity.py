@@ -863,6 +863,66 @@ def test_algorithm1_rollout_driver(mode, lag, sink, window):
     assert [r.emitted for r in ro.records if r.emitted >= 0] == list(range(n_blocks))
 
 
+@pytest.mark.parametrize("mode", [BI, CA])
+def test_algorithm1_rollout_driver_with_the_publishing_projection(mode):
+    """The same 13-block rollout with the layer's QKV projection in it, in the three-launch form:
+    every iteration's K/V are published by the projection's own epilogue (layer_qkv_publish) and
+    the attention kernel rotates the queries.  The oracle projects in fp64 (no rounding of q, k,
+    v), rotates, attends; cache snapshots are compared after every iteration, outputs to the bars
+    of the layer pipeline test (q, k, v are rounded to bf16 on the GPU side: relative L2 1e-2)."""
+    import torch
+    from paper_2511_20426_amd.runner import CascadePool
+    from paper_2511_20426_amd.rollout import CascadeRollout
+    w = W.small_variant(W.CONFIGS["c5_wan1p3b_rollout"], heads=2, grid_h=6, grid_w=9, sink_blocks=1, window_blocks=2)
+    L, H, D = w.block_tokens, w.heads, w.head_dim
+    width, n_blocks = H * D, 13
+    _say(f"alg1 rollout with the publishing projection: L={L} width={width} mode={mode}")
+    _, w_qkv = W.draw_linear(1, 3 * width, width, seed=91)
+    wq_t = Hn.to_torch(w_qkv, "bf16")
+    pool = CascadePool.for_workload(w)
+    xs, outs = {}, {}
+
+    def publish_fn(batch, epoch):
+        it = len(ro.records)
+        for i in range(len(batch)):
+            xs[(it, i)] = W.draw_linear(L, 3 * width, width, seed=1000 + 10 * it + i, x_scale=0.5)[0]
+        x = torch.cat([Hn.to_torch(xs[(it, i)], "bf16") for i in range(len(batch))])
+        return pool.qkv_publish(x, wq_t, [g for g, _, _ in batch], [t for _, _, t in batch], epoch)
+
+    def out_fn(g, ti, o):
+        outs.setdefault(len(ro.records), []).append(Hn.from_torch(o, w.dtype))
+
+    ro = CascadeRollout(pool, n_blocks, W.TIMESTEPS, out_fn=out_fn, publish_fn=publish_fn, mode=mode)
+    trace = orc.algorithm1_trace(n_blocks, 5)
+    cache = orc.KVCacheOracle(w.sink_blocks, w.window_blocks, w.max_inflight, w.pages_per_block, H)
+    pos = lambda g: orc.token_positions(g, w.frames_per_block, w.grid_h, w.grid_w)
+    wf = W.to_f64(w_qkv)
+    final_kv = {}
+    for it, (b, tau, d, batch) in enumerate(trace):
+        rec = ro.step()
+        torch.cuda.synchronize()
+        assert [(g, ti) for g, ti, _ in rec.batch] == batch
+        proj = {}
+        for i, (g, ti) in enumerate(batch):
+            cache.append(g, W.TIMESTEPS[ti], 0)
+            qkv = orc.layer_linear(W.to_f64(xs[(it, i)]), wf).reshape(L, 3, H, D)
+            proj[g] = (orc.rope3d(qkv[:, 0], pos(g), w.rope_dims, w.rope_theta),
+                       orc.rope3d(qkv[:, 1], pos(g), w.rope_dims, w.rope_theta), qkv[:, 2])
+            if ti == len(W.TIMESTEPS) - 1:
+                final_kv[g] = proj[g][1:]
+        infl = [g for g, _ in batch]
+        order, states, _ = cache.kv_order(infl)
+        kb = [proj[g][1] if st == orc.NOISY else final_kv[g][0] for g, st in zip(order, states)]
+        vb = [proj[g][2] if st == orc.NOISY else final_kv[g][1] for g, st in zip(order, states)]
+        ref = _cat(orc.cascade_attention([proj[g][0] for g in infl], kb, vb, orc.visibility(states, order, infl, mode)))
+        got = _cat(outs[it])
+        Hn.assert_close(got, ref, "bf16", f"alg1 + projection, iteration {it}",
+                        max_abs=0.05 * float(np.abs(ref).max()) + 1e-3, rel=1e-2)
+        orc.rollout_finish(cache, b, [(g, W.TIMESTEPS[ti]) for g, ti in batch])
+        assert [s.astuple() for s in pool.ctx.kv_cache_snapshot()] == cache.snapshot()
+    assert ro.step() is None
+
+
 def test_mfma_microbench_reports_a_plausible_ceiling():
     """The MFMA-only loop: below the nominal peak, above half of it, clock within the chip's range;
     zero operands switch less and must not be slower than random ones."""
