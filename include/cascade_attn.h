@@ -235,8 +235,9 @@ int32_t ca_debug_visibility(const ca_ctx* ctx, const int64_t* inflight_block_ids
  * row-major with row strides ldx, ldw, ldy in elements (multiples of 8, 16-byte aligned bases);
  * nothing is allocated and nothing but y[0..m_rows) x [0..n_out) is written.  The QKV projection
  * writes [tokens][3][heads][head_dim] rows that rope3d_apply and kv_cache_append take as strided
- * views.  Supported shapes: n_out a multiple of 256, k_in a multiple of 128 (CA_EUNSUPPORTED
- * otherwise); m_rows is free (0: nothing is done, CA_OK). */
+ * views.  Supported shapes: n_out a multiple of 8, k_in a multiple of 128 (CA_EUNSUPPORTED
+ * otherwise); m_rows is free (0: nothing is done, CA_OK).  Tiles are 256 x 256: an n_out that is not
+ * a multiple of 256 costs the padding of its last column tile. */
 int32_t layer_linear_bf16(const void* x_dev, const void* w_dev, void* y_dev, int64_t m_rows, int32_t n_out,
                           int32_t k_in, int64_t ldx, int64_t ldw, int64_t ldy, void* hip_stream);
 

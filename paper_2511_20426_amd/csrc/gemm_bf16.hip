@@ -89,7 +89,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
   for (int i = 0; i < 8; ++i) {
     const int row = (wave * 8 + i) * 8 + (lane >> 3);
     const int c = (lane & 7) ^ ((row >> 1) & 7);
-    offw[i] = uint32_t(int64_t(row) * a.ldw * 2 + c * 16);
+    const int nrow = min(n0 + row, a.N - 1) - n0;                // rows of w past n_out re-read its last row
+    offw[i] = uint32_t(int64_t(nrow) * a.ldw * 2 + c * 16);
     const int mrow = min(m0 + row, m_end - 1) - m0;              // rows past the block's end re-read its last row
     offx[i] = uint32_t(int64_t(mrow) * a.ldx * 2 + c * 16);
   }
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_kernel(GemmArgs a) {
       const u32x4 v = *reinterpret_cast<const u32x4*>(mine + row * kEpiRow + c * 16);
       const int gm = m0 + wm * 128 + row;
       // the result passes through once: keep it from displacing the operand tiles in the caches
-      if (gm < m_end)
+      if (gm < m_end && n0 + wn * 128 + c * 8 < a.N)            // n_out is a multiple of 8: a chunk is inside or outside
         __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(a.y + int64_t(gm) * a.ldy + n0 + wn * 128 + c * 8));
     }
     return;
@@ -231,7 +232,7 @@ namespace {
 
 int32_t check_gemm_shape(int64_t M, int32_t N, int32_t K, int64_t ldx, int64_t ldw, int64_t ldy) {
   if (M < 0) return CA_EINVAL;
-  if (M > (int64_t(1) << 30) || N < kTile || N % kTile != 0 || K < 128 || K % 128 != 0) return CA_EUNSUPPORTED;
+  if (M > (int64_t(1) << 30) || N < 8 || N % 8 != 0 || K < 128 || K % 128 != 0) return CA_EUNSUPPORTED;
   if (ldx < K || ldw < K || ldy < 0 || ldx % 8 != 0 || ldw % 8 != 0 || ldy % 8 != 0) return CA_EINVAL;
   if (ldx * 2 * kTile >= (int64_t(1) << 31) || ldw * 2 * kTile >= (int64_t(1) << 31)) return CA_EUNSUPPORTED;
   return CA_OK;
@@ -239,7 +240,7 @@ int32_t check_gemm_shape(int64_t M, int32_t N, int32_t K, int64_t ldx, int64_t l
 
 template <bool kPublish>
 int32_t enqueue_gemm(GemmArgs& a, void* stream) {
-  a.tiles_n = a.N / kTile;
+  a.tiles_n = (a.N + kTile - 1) / kTile;
   a.sb_cols = (a.tiles_n + kSbCols - 1) / kSbCols;
   a.n_sb = ((a.tiles_m + kSbRows - 1) / kSbRows) * a.sb_cols;
   const unsigned rounds = unsigned((a.n_sb + 7) / 8);

@@ -59,7 +59,7 @@ int32_t attn_bf16_variant_ok(int variant) { return variant == 0 || variant == 1 
 int32_t run_mfma_microbench(int, int, void*, size_t, void*, double*, double*) { return CA_OK; }
 int32_t launch_gemm_bf16(const void*, const void*, void*, int64_t, int32_t n, int32_t k, int64_t, int64_t, int64_t,
                          void*) {
-  return (n % 256 || k % 128) ? CA_EUNSUPPORTED : CA_OK;
+  return (n % 8 || k % 128) ? CA_EUNSUPPORTED : CA_OK;
 }
 int32_t launch_gemm_qkv_publish(const RopeGeom& g, int32_t n_blocks, int32_t block_tokens, int32_t pages, const int32_t* slot,
                                 const int64_t* first_frame, const void* x, int64_t ldx, const void* w, int64_t, int32_t k,

@@ -957,7 +957,8 @@ def _linear_check(got, x, w, rows, what):
     assert worst <= 1.0, what
 
 
-@pytest.mark.parametrize("M,N,K,pad", [(300, 256, 128, 0), (1000, 512, 384, 8), (257, 768, 1024, 24), (1, 256, 128, 0)])
+@pytest.mark.parametrize("M,N,K,pad", [(300, 256, 128, 0), (1000, 512, 384, 8), (257, 768, 1024, 24), (1, 256, 128, 0),
+                                       (300, 8, 128, 0), (517, 328, 256, 8), (40, 1000, 128, 16)])
 def test_layer_linear_small_full(M, N, K, pad):
     """Every output element; M not a multiple of the 256-row tile, K of several loop trips,
     row strides larger than the row (pad) for all three matrices."""
@@ -999,7 +1000,7 @@ def test_layer_linear_rejects_unsupported_shapes():
     from paper_2511_20426_amd import binding as B
     t = torch.zeros((512, 512), dtype=torch.bfloat16, device="cuda:0")
     p = t.data_ptr()
-    for args, code in (((p, p, p, 256, 200, 128, 512, 512, 512), B.CA_EUNSUPPORTED),   # n_out not a multiple of 256
+    for args, code in (((p, p, p, 256, 204, 128, 512, 512, 512), B.CA_EUNSUPPORTED),   # n_out not a multiple of 8
                        ((p, p, p, 256, 256, 96, 512, 512, 512), B.CA_EUNSUPPORTED),    # k_in not a multiple of 128
                        ((p, p, p, 256, 256, 128, 64, 512, 512), B.CA_EINVAL),          # row stride shorter than the row
                        ((p, p, p + 2, 256, 256, 128, 512, 512, 512), B.CA_EINVAL),     # misaligned
