@@ -220,6 +220,15 @@ def time_streaming_protocol(torch, W, B, w, blocks=13):
             out = {"iterations_per_s": streaming_rate(recs), "iteration_ms": [r.ms for r in recs if r.emitted in (7, 8)],
                    "blocks_per_s_whole_rollout": blocks / (sum(r.ms for r in recs) * 1e-3), "iterations": len(recs)}
         del ro, pool
+    # the cascade types as schedules (Fig. 7: block j enters `lag` iterations after block j-1; lag 5, 3, 2, 1
+    # keep 1, 2, 3, 5 blocks in flight): the whole 13-block rollout, ramp-up and drain included
+    out["cascade_types"] = {}
+    for lag, name in ((5, "P1"), (3, "P2"), (2, "P3"), (1, "P4")):
+        pool = CascadePool.for_workload(w, device=dev)
+        ro = CascadeRollout(pool, blocks, W.TIMESTEPS, lambda g, ti, it, i: bank[i], mode=B.CA_BIDIRECTIONAL, timed=True, lag=lag)
+        recs = ro.run()
+        out["cascade_types"][name] = {"lag": lag, "iterations": len(recs), "blocks_per_s": blocks / (sum(r.ms for r in recs) * 1e-3)}
+        del ro, pool
     return out
 
 
