@@ -343,7 +343,7 @@ def test_bf16_seeded_random_shapes(case):
 def test_bf16_seeded_random_shapes_wide(case):
     """Wider draws: up to 24 heads and 1620 tokens per block (launches with more work items than
     CUs, i.e. split KV walks and the merge kernel), with or without a sink block, nominal or
-    peaked inputs, plus a random share of the same forward."""
+    peaked inputs, plus the forward that rotates Q itself and a random share of the same forward."""
     rng = np.random.default_rng([4242, case])
     fpb = int(rng.integers(1, 4))
     gh, gw = int(rng.integers(2, 21)), int(rng.integers(2, 28))
@@ -372,6 +372,9 @@ def test_bf16_seeded_random_shapes_wide(case):
     # logits grow with scale^2 and outputs with scale: the bars of the peaked variant, interpolated
     grow = (scale / 0.5) ** 1.3
     Hn.assert_close(out, ref, "bf16", f"wide random shape {case}", max_abs=2e-2 * grow, rel=5e-3 * grow, bound=bound)
+    fused = Hn.gpu_forward_rope(w, pool, q, infl, mode, packed=bool(case % 2))
+    Hn.assert_close(fused, ref, "bf16", f"wide random shape {case}, Q rotated in the kernel", max_abs=2e-2 * grow,
+                    rel=5e-3 * grow, bound=bound)
     if ni > 1:
         f0 = int(rng.integers(0, ni))
         cnt = int(rng.integers(1, ni - f0 + 1))
