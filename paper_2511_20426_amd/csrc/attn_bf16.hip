@@ -306,35 +306,36 @@ __global__ __launch_bounds__(256, 1) void attn_bf16_kernel(AttnArgs a) {
 
 
 // Combines the partial results of the split work items: for every row, the partials are brought
-// to the largest of their exponent references, summed and normalised.
+// to the largest of their exponent references, summed and normalised.  Eight workgroups per tile
+// (blockIdx.y picks 32 of its rows); 32 threads share a row (four dims each), so that a row of a
+// partial tile is read as 512 contiguous bytes and a result row is written as 256.
 __global__ __launch_bounds__(256) void merge_partials_kernel(AttnArgs a) {
   const int xcd = blockIdx.x / a.split_items, sidx = blockIdx.x % a.split_items;
   const WorkItem wi = decode_item(a, xcd, a.full_items + sidx);
   if (wi.h < 0) return;
-  const int r = threadIdx.x, row = wi.row0 + r;
-  if (row >= wi.rows_end) return;
-  const float* part = a.partials + size_t(xcd * a.split_items + sidx) * a.split * kPartialFloats + r * kPartialRow;
-  float m = -INFINITY;
-  for (int c = 0; c < a.split; ++c) m = fmaxf(m, part[c * kPartialFloats + 128]);
-  float wgt[8], l = 0.f;
-  for (int c = 0; c < a.split; ++c) {
-    wgt[c] = __builtin_amdgcn_exp2f(part[c * kPartialFloats + 128] - m);
-    l += wgt[c] * part[c * kPartialFloats + 129];
-  }
-  const float inv = 1.0f / l;
-  uint16_t* op = a.o + (int64_t(row) * a.heads + wi.h) * 128;
-  for (int d = 0; d < 128; d += 8) {
-    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < a.split; ++c) {
-      const float4 x = *reinterpret_cast<const float4*>(part + c * kPartialFloats + d);
-      const float4 y = *reinterpret_cast<const float4*>(part + c * kPartialFloats + d + 4);
-      acc[0] += wgt[c] * x.x; acc[1] += wgt[c] * x.y; acc[2] += wgt[c] * x.z; acc[3] += wgt[c] * x.w;
-      acc[4] += wgt[c] * y.x; acc[5] += wgt[c] * y.y; acc[6] += wgt[c] * y.z; acc[7] += wgt[c] * y.w;
-    }
-    u32x4 w;
+  const int sub = threadIdx.x >> 5, d = 4 * (threadIdx.x & 31);
+  const float* tile = a.partials + size_t(xcd * a.split_items + sidx) * a.split * kPartialFloats;
 #pragma unroll
-    for (int j = 0; j < 4; ++j) w[j] = pack2(acc[2 * j] * inv, acc[2 * j + 1] * inv);
-    *reinterpret_cast<u32x4*>(op + d) = w;
+  for (int pass = 0; pass < 4; ++pass) {
+    const int r = int(blockIdx.y) * 32 + pass * 8 + sub;
+    const int row = wi.row0 + r;
+    if (row >= wi.rows_end) break;                       // rows only grow from here
+    const float* part = tile + r * kPartialRow;
+    float m = -INFINITY;
+    for (int c = 0; c < a.split; ++c) m = fmaxf(m, part[c * kPartialFloats + 128]);
+    float l = 0.f;
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < a.split; ++c) {
+      const float wgt = __builtin_amdgcn_exp2f(part[c * kPartialFloats + 128] - m);
+      l += wgt * part[c * kPartialFloats + 129];
+      const float4 x = *reinterpret_cast<const float4*>(part + c * kPartialFloats + d);
+      acc.x += wgt * x.x; acc.y += wgt * x.y; acc.z += wgt * x.z; acc.w += wgt * x.w;
+    }
+    const float inv = 1.0f / l;
+    u32x2 w;
+    w[0] = pack2(acc.x * inv, acc.y * inv);
+    w[1] = pack2(acc.z * inv, acc.w * inv);
+    *reinterpret_cast<u32x2*>(a.o + (int64_t(row) * a.heads + wi.h) * 128 + d) = w;
   }
 }
 
@@ -425,7 +426,7 @@ int32_t enqueue_attn_bf16(const AttnArgs& a, bool rope_q, void* stream) {
   else
     hipLaunchKernelGGL(attn_bf16_kernel<false>, grid, dim3(256), 4 * kPageBytes, static_cast<hipStream_t>(stream), a);
   if (a.split > 1)
-    hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(8 * a.split_items)), dim3(256), 0,
+    hipLaunchKernelGGL(merge_partials_kernel, dim3((unsigned)(8 * a.split_items), kRowsPerWg / 32), dim3(256), 0,
                        static_cast<hipStream_t>(stream), a);
   return finish_launch("attn_bf16.hip");
 }
